@@ -1,0 +1,150 @@
+/*
+ * libpevlm -- prefill attention of PEVLM (parallel encoding for vision-language models) for
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The method (paper Sec. "Parallel Encoding"): a long video token sequence is split into a Sink
+ * Block (prompt + first frames), frame-aligned Context Blocks and a trailing Question Block
+ * (Sec. "Partitioning Strategy").  Every token is rotated at the position it has in the whole
+ * sequence -- never re-based per block (Sec. "Position Encoding").  Attention is standard softmax
+ * attention (Eq. 1) restricted as in Sec. "Formulations":
+ *     Attn_s   = f(Q_s,   K_s,            V_s)               (Eq. 3)  sink rows
+ *     Attn_c_i = f(Q_c_i, K_{s + c_i},    V_{s + c_i})       (Eq. 4)  block i sees sink + itself
+ *     Attn_q   = f(Q_q,   K_{s+c_all+q},  V_{s+c_all+q})     (Eq. 5)  question sees everything
+ * and is causal inside every region (key index <= query index).  Eq. 4 is taken with the key set
+ * "sink plus the block itself", which is what the operation count OP_ContextBlock = 2HB(S+B)
+ * (Eq. 8) and the O(L) complexity claim describe.
+ *
+ * Data layout (all tensors, DEVICE memory, caller-owned): token-major packed,
+ *     q, out : [T][n_q_heads][head_dim]      k, v : [T][n_kv_heads][head_dim]
+ * contiguous, element type given by pevlm_heads.dtype, base pointers 16-byte aligned.  Sequence s
+ * owns packed rows cu_seqlens[s] .. cu_seqlens[s+1]-1 in the order
+ *     [ sink (S) | block 0 | ... | block N-1 (context, C tokens in total) | question (Q) ].
+ *
+ * Conventions shared by every call:
+ *   - Descriptor structs and the arrays they point to are HOST memory, read during the call only.
+ *   - Work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as void*;
+ *     NULL = the default stream).  No call synchronises with the device, allocates or frees
+ *     device memory, or keeps device state between calls.  Scratch memory is a caller-provided
+ *     DEVICE workspace sized by the matching *_workspace_bytes query (256-byte aligned).
+ *   - Every call returns a pevlm_status; on failure nothing has been enqueued unless the status is
+ *     PEVLM_ERR_HIP, and pevlm_last_error() describes the failure.
+ *   - Results are bitwise reproducible for fixed arguments (no atomics, fixed split counts).
+ */
+#ifndef PEVLM_H
+#define PEVLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PEVLM_OK = 0,
+    PEVLM_ERR_INVALID_ARG = 1,        /* null / misaligned pointer, inconsistent layout, bad head map */
+    PEVLM_ERR_UNSUPPORTED = 2,        /* head_dim or dtype outside what the kernels cover          */
+    PEVLM_ERR_WORKSPACE_TOO_SMALL = 3,
+    PEVLM_ERR_HIP = 4                 /* a HIP runtime call failed (launch, device query)          */
+} pevlm_status;
+
+typedef enum {
+    PEVLM_F32 = 0,  /* fp32 storage and arithmetic (plain FMA kernels; the numerical anchor)       */
+    PEVLM_BF16 = 1  /* bf16 storage, bf16 MFMA with fp32 accumulation and fp32 softmax             */
+} pevlm_dtype;
+
+/* Partition of every packed sequence (Sec. "Partitioning Strategy").  num_blocks = ceil(C / B);
+ * the last context block holds C - (num_blocks-1)*B tokens and may be shorter than B.  S, C and Q
+ * may each be 0.  Required: S + C + Q == cu_seqlens[s+1] - cu_seqlens[s], cu_seqlens[0] == 0. */
+typedef struct {
+    int32_t num_seqs;           /* >= 1 */
+    const int32_t *cu_seqlens;  /* [num_seqs + 1] */
+    const int32_t *sink_len;    /* [num_seqs]  S >= 0 */
+    const int32_t *block_len;   /* [num_seqs]  B >= 1 (ignored where C == 0) */
+    const int32_t *ctx_len;     /* [num_seqs]  C >= 0 */
+    const int32_t *query_len;   /* [num_seqs]  Q >= 0 */
+} pevlm_layout;
+
+typedef struct {
+    int32_t n_q_heads;            /* Hq */
+    int32_t n_kv_heads;           /* Hkv, Hq % Hkv == 0 */
+    int32_t head_dim;             /* D: 64 or 128 */
+    const int32_t *kv_head_of_q;  /* HOST [Hq] KV head of each query head, or NULL = h / (Hq/Hkv) */
+    pevlm_dtype dtype;
+    float softmax_scale;          /* <= 0 selects 1/sqrt(head_dim) (Eq. 1) */
+} pevlm_heads;
+
+/*
+ * Sequential rotary position embedding (Sec. "Position Encoding"), in place on q [T][Hq][D] and
+ * k [T][Hkv][D] (either may be NULL to skip it).  Token t of sequence s is rotated at
+ * pos = t - cu_seqlens[s] + pos_offset[s] (pos_offset: HOST [num_seqs] or NULL = 0): positions run
+ * through sink, every context block and the question without restarting.  Rotate-half pairing:
+ * (x[i], x[i+D/2]) turns by pos * rope_base^(-2i/D).  Angles are formed in fp64 and reduced before
+ * the fp32 sine/cosine; results are rounded once to the storage type.
+ */
+pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const pevlm_heads *heads,
+                            double rope_base, const int32_t *pos_offset, void *stream);
+
+/*
+ * Block-parallel prefill attention: rows of the sink (Eq. 3) and of every context block (Eq. 4).
+ * q and k must already be rotated.  Writes out rows of the sink and context regions only;
+ * question rows of `out` (and `lse`) are left untouched.  lse: DEVICE fp32 [T][Hq] natural-log
+ * sum-exp of the scaled scores per written row, or NULL.  A tile work list that names only
+ * (query tile, sink keys, own-block keys up to the diagonal) is built on the device into the
+ * workspace; cross-block tiles are never enumerated.  A dense causal attention over a sequence is
+ * the layout S = 0, C = L, B = L, Q = 0.
+ */
+size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads);
+pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                                      const pevlm_layout *layout, const pevlm_heads *heads,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Question attention (Eq. 5): every question row attends to all earlier tokens of its sequence
+ * (sink, all context blocks, earlier question tokens).  The key range is cut into num_splits
+ * parts (0 = chosen from the layout; 1..PEVLM_MAX_SPLITS otherwise) that are processed by
+ * different workgroups into fp32 partials (max, sum, weighted values) in the workspace and then
+ * merged with the log-sum-exp identity.  Writes question rows of `out` (and `lse`) only.
+ */
+#define PEVLM_MAX_SPLITS 64
+size_t pevlm_query_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits);
+pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                              const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* Message of the last failure on the calling thread (static storage, never NULL). */
+const char *pevlm_last_error(void);
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t pevlm_version(void);
+
+/* ---- host-side utilities (no device access; usable on a machine without a GPU) ---- */
+
+/* One unit of work of the block-prefill kernel: a tile of at most tile_rows query rows that lie
+ * in one region (the sink, or one context block) plus the two key ranges it needs.  Indices are
+ * packed token rows.  Keys [full_start, full_start + full_len) are all visible to every row of
+ * the tile (the sink, for a context tile); keys [diag_start, diag_start + diag_len) are visible to
+ * row i iff key <= i (own region up to the tile's last row). */
+typedef struct {
+    int32_t q_start, q_rows;
+    int32_t full_start, full_len;
+    int32_t diag_start, diag_len;
+    int32_t seq, reserved;
+} pevlm_work_item;
+
+/* Rows per query tile used by the bf16 block-prefill kernel. */
+int32_t pevlm_prefill_tile_rows(void);
+/* Enumerates, on the host, exactly the work list the device builder writes.  Returns the number
+ * of items (also when items == NULL or capacity is too small: then nothing beyond capacity is
+ * written), or -1 for an invalid layout. */
+int64_t pevlm_prefill_worklist_host(const pevlm_layout *layout, int32_t tile_rows,
+                                    pevlm_work_item *items, int64_t capacity);
+/* Visible (query, key) pairs per head implied by the layout, split by region; the causal closed
+ * forms behind the paper's operation counts (Eq. 6-10).  Any output pointer may be NULL.
+ * Returns PEVLM_OK or PEVLM_ERR_INVALID_ARG. */
+pevlm_status pevlm_visible_pairs(const pevlm_layout *layout, int64_t *sink_pairs, int64_t *block_pairs,
+                                 int64_t *question_pairs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEVLM_H */

@@ -1,0 +1,26 @@
+"""PEVLM prefill attention for AMD MI355X (gfx950): Python binding of libpevlm.so.
+
+The binding only marshals arguments; every step of the path (sequential RoPE, block-parallel
+prefill attention, split-KV question attention + merge) runs in the HIP kernels behind the C ABI
+declared in include/pevlm.h.  There is no CPU fallback: loading fails if the library is missing.
+"""
+from .binding import (  # noqa: F401
+    Heads,
+    Layout,
+    PevlmError,
+    WorkItem,
+    lib_path,
+    load_library,
+    pevlm_block_prefill_attn,
+    pevlm_block_prefill_workspace_bytes,
+    pevlm_last_error,
+    pevlm_prefill_tile_rows,
+    pevlm_prefill_worklist_host,
+    pevlm_query_attn,
+    pevlm_query_workspace_bytes,
+    pevlm_query_worklist_host,
+    pevlm_rope_seq,
+    pevlm_version,
+    pevlm_visible_pairs,
+)
+from .cost_model import useful_flops  # noqa: F401

@@ -1,0 +1,378 @@
+// Host side of libpevlm: argument validation, workspace carving, work-list builders and launches.
+// Entry points are documented in include/pevlm.h.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "common.h"
+
+namespace pevlm {
+
+static thread_local char g_err[512] = "no error";
+
+static pevlm_status fail(pevlm_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static pevlm_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(PEVLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
+
+static pevlm_status check_layout(const pevlm_layout *lay)
+{
+    if (!lay) return fail(PEVLM_ERR_INVALID_ARG, "layout is NULL");
+    if (lay->num_seqs < 1) return fail(PEVLM_ERR_INVALID_ARG, "num_seqs must be >= 1");
+    if (!lay->cu_seqlens || !lay->sink_len || !lay->block_len || !lay->ctx_len || !lay->query_len)
+        return fail(PEVLM_ERR_INVALID_ARG, "layout array is NULL");
+    if (lay->cu_seqlens[0] != 0) return fail(PEVLM_ERR_INVALID_ARG, "cu_seqlens[0] must be 0");
+    for (int32_t s = 0; s < lay->num_seqs; ++s) {
+        int64_t len = (int64_t)lay->cu_seqlens[s + 1] - lay->cu_seqlens[s];
+        if (len < 0) return fail(PEVLM_ERR_INVALID_ARG, "cu_seqlens decreases at sequence %d", s);
+        if (lay->sink_len[s] < 0 || lay->ctx_len[s] < 0 || lay->query_len[s] < 0)
+            return fail(PEVLM_ERR_INVALID_ARG, "negative region length in sequence %d", s);
+        if (lay->ctx_len[s] > 0 && lay->block_len[s] < 1)
+            return fail(PEVLM_ERR_INVALID_ARG, "block_len must be >= 1 in sequence %d", s);
+        if ((int64_t)lay->sink_len[s] + lay->ctx_len[s] + lay->query_len[s] != len)
+            return fail(PEVLM_ERR_INVALID_ARG, "sink+ctx+query != sequence length in sequence %d", s);
+    }
+    return PEVLM_OK;
+}
+
+static pevlm_status check_heads(const pevlm_heads *h, HeadTable *tab)
+{
+    if (!h) return fail(PEVLM_ERR_INVALID_ARG, "heads is NULL");
+    if (h->n_q_heads < 1 || h->n_kv_heads < 1 || h->n_q_heads % h->n_kv_heads != 0)
+        return fail(PEVLM_ERR_INVALID_ARG, "need n_q_heads %% n_kv_heads == 0 (got %d / %d)", h->n_q_heads,
+                    h->n_kv_heads);
+    if (h->n_q_heads > kMaxHeads) return fail(PEVLM_ERR_UNSUPPORTED, "more than %d query heads", kMaxHeads);
+    if (h->dtype != PEVLM_F32 && h->dtype != PEVLM_BF16) return fail(PEVLM_ERR_UNSUPPORTED, "unknown dtype %d", (int)h->dtype);
+    if (h->head_dim != 64 && h->head_dim != 128)
+        return fail(PEVLM_ERR_UNSUPPORTED, "head_dim %d not in {64, 128}", h->head_dim);
+    int32_t G = h->n_q_heads / h->n_kv_heads;
+    for (int32_t i = 0; i < h->n_q_heads; ++i) {
+        int32_t g = h->kv_head_of_q ? h->kv_head_of_q[i] : i / G;
+        if (g < 0 || g >= h->n_kv_heads) return fail(PEVLM_ERR_INVALID_ARG, "kv_head_of_q[%d] = %d out of range", i, g);
+        if (tab) tab->kv_of_q[i] = (uint8_t)g;
+    }
+    if (tab) {  // schedule order: heads grouped by KV head so neighbours share K/V in L2
+        int32_t n = 0;
+        for (int32_t g = 0; g < h->n_kv_heads; ++g)
+            for (int32_t i = 0; i < h->n_q_heads; ++i)
+                if (tab->kv_of_q[i] == g) tab->head_order[n++] = (uint8_t)i;
+    }
+    return PEVLM_OK;
+}
+
+static float scale_of(const pevlm_heads *h)
+{
+    return h->softmax_scale > 0.f ? h->softmax_scale : (float)(1.0 / sqrt((double)h->head_dim));
+}
+
+static int32_t tile_rows_of(const pevlm_heads *h) { return h->dtype == PEVLM_BF16 ? kTileRowsBf16 : kTileRowsF32; }
+
+// Fills the chunk table for sequences [s0, s0 + n).
+static void fill_table(const pevlm_layout *lay, int32_t s0, int32_t n, const int32_t *pos_offset, SeqTable *t)
+{
+    memset(t, 0, sizeof *t);
+    t->num_seqs = n;
+    t->seq_index0 = s0;
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t s = s0 + i;
+        t->start[i] = lay->cu_seqlens[s];
+        t->sink[i] = lay->sink_len[s];
+        t->block[i] = lay->ctx_len[s] > 0 ? lay->block_len[s] : 1;
+        t->ctx[i] = lay->ctx_len[s];
+        t->query[i] = lay->query_len[s];
+        t->pos_offset[i] = pos_offset ? pos_offset[s] : 0;
+    }
+}
+
+static int64_t count_prefill_items(const pevlm_layout *lay, int32_t tile_rows)
+{
+    int64_t n = 0;
+    for (int32_t s = 0; s < lay->num_seqs; ++s)
+        n += prefill_items_of_seq(lay->sink_len[s], lay->ctx_len[s] > 0 ? lay->block_len[s] : 1, lay->ctx_len[s], tile_rows);
+    return n;
+}
+
+static int64_t count_query_tiles(const pevlm_layout *lay, int32_t tile_rows)
+{
+    int64_t n = 0;
+    for (int32_t s = 0; s < lay->num_seqs; ++s) n += query_tiles_of_seq(lay->query_len[s], tile_rows);
+    return n;
+}
+
+static int64_t total_query_rows(const pevlm_layout *lay)
+{
+    int64_t n = 0;
+    for (int32_t s = 0; s < lay->num_seqs; ++s) n += lay->query_len[s];
+    return n;
+}
+
+// Split count when the caller leaves it to the library: enough workgroups to cover the chip a few
+// times, but no split shorter than a few key tiles.
+static int32_t auto_splits(const pevlm_layout *lay, const pevlm_heads *h)
+{
+    int64_t tiles = count_query_tiles(lay, tile_rows_of(h));
+    if (tiles == 0) return 1;
+    int64_t max_len = 0;
+    for (int32_t s = 0; s < lay->num_seqs; ++s)
+        max_len = std::max<int64_t>(max_len, (int64_t)lay->cu_seqlens[s + 1] - lay->cu_seqlens[s]);
+    int64_t want = (1024 + tiles * h->n_q_heads - 1) / (tiles * h->n_q_heads);
+    int64_t cap = std::max<int64_t>(1, max_len / 512);
+    return (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, cap), PEVLM_MAX_SPLITS));
+}
+
+struct QueryPlan {
+    int32_t num_splits, tile_rows;
+    int64_t n_items, total_q;
+    size_t off_items, off_qrow, off_ml, off_acc, bytes;
+};
+
+static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits)
+{
+    QueryPlan p;
+    p.tile_rows = tile_rows_of(h);
+    p.num_splits = num_splits > 0 ? num_splits : auto_splits(lay, h);
+    p.total_q = total_query_rows(lay);
+    p.n_items = count_query_tiles(lay, p.tile_rows) * p.num_splits;
+    size_t off = 0;
+    p.off_items = off;
+    off += align256((size_t)p.n_items * sizeof(pevlm_work_item));
+    p.off_qrow = off;
+    off += align256((size_t)p.total_q * sizeof(int32_t));
+    p.off_ml = off;
+    off += align256((size_t)p.num_splits * p.total_q * h->n_q_heads * 2 * sizeof(float));
+    p.off_acc = off;
+    off += align256((size_t)p.num_splits * p.total_q * h->n_q_heads * h->head_dim * sizeof(float));
+    p.bytes = off;
+    return p;
+}
+
+}  // namespace pevlm
+
+using namespace pevlm;
+
+extern "C" {
+
+const char *pevlm_last_error(void) { return g_err; }
+int32_t pevlm_version(void) { return 100; }
+int32_t pevlm_prefill_tile_rows(void) { return kTileRowsBf16; }
+
+pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const pevlm_heads *heads,
+                            double rope_base, const int32_t *pos_offset, void *stream)
+{
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    if (!(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
+    if ((q && !aligned16(q)) || (k && !aligned16(k))) return fail(PEVLM_ERR_INVALID_ARG, "q/k must be 16-byte aligned");
+    if (layout->cu_seqlens[layout->num_seqs] == 0 || (!q && !k)) return PEVLM_OK;
+    for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
+        SeqTable tab;
+        fill_table(layout, s0, std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0), pos_offset, &tab);
+        hipError_t e = launch_rope(q, k, tab, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
+                                   heads->dtype == PEVLM_BF16, rope_base, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, "rope launch");
+    }
+    return PEVLM_OK;
+}
+
+size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
+{
+    if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
+    return align256((size_t)count_prefill_items(layout, tile_rows_of(heads)) * sizeof(pevlm_work_item)) + 256;
+}
+
+pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                                      const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    AttnParams p;
+    memset(&p, 0, sizeof p);
+    st = check_heads(heads, &p.heads);
+    if (st != PEVLM_OK) return st;
+    if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
+        return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    int32_t tile_rows = tile_rows_of(heads);
+    int64_t n_items = count_prefill_items(layout, tile_rows);
+    if (n_items == 0) return PEVLM_OK;
+    if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
+    size_t need = pevlm_block_prefill_workspace_bytes(layout, heads);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
+        return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "prefill workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    hipStream_t hs = (hipStream_t)stream;
+    pevlm_work_item *items = (pevlm_work_item *)workspace;
+    int32_t offset = 0;
+    for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
+        SeqTable tab;
+        int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
+        fill_table(layout, s0, n, nullptr, &tab);
+        for (int32_t i = 0; i < n; ++i)
+            tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], tile_rows);
+        if (tab.item_base[n] > 0) {
+            hipError_t e = launch_build_prefill_items(tab, tile_rows, items, offset, hs);
+            if (e != hipSuccess) return hip_fail(e, "work-list builder launch");
+        }
+        offset += tab.item_base[n];
+    }
+    p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
+    p.items = items;
+    p.n_items = (int32_t)n_items;
+    p.n_q_heads = heads->n_q_heads;
+    p.n_kv_heads = heads->n_kv_heads;
+    p.scale = scale_of(heads);
+    hipError_t e = heads->dtype == PEVLM_BF16 ? launch_attn_bf16(p, heads->head_dim, false, hs)
+                                              : launch_attn_f32(p, heads->head_dim, false, hs);
+    if (e != hipSuccess) return hip_fail(e, "block-prefill launch");
+    return PEVLM_OK;
+}
+
+size_t pevlm_query_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)
+{
+    if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
+    if (num_splits < 0 || num_splits > PEVLM_MAX_SPLITS) return 0;
+    return plan_query(layout, heads, num_splits).bytes + 256;
+}
+
+pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                              const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    AttnParams p;
+    memset(&p, 0, sizeof p);
+    st = check_heads(heads, &p.heads);
+    if (st != PEVLM_OK) return st;
+    if (num_splits < 0 || num_splits > PEVLM_MAX_SPLITS)
+        return fail(PEVLM_ERR_INVALID_ARG, "num_splits must be in [0, %d]", PEVLM_MAX_SPLITS);
+    if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
+        return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    QueryPlan plan = plan_query(layout, heads, num_splits);
+    if (plan.total_q == 0) return PEVLM_OK;
+    if (plan.n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
+    if (!workspace || workspace_bytes < plan.bytes || ((uintptr_t)workspace & 255))
+        return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "query workspace needs %zu bytes, 256-byte aligned (got %zu)",
+                    plan.bytes + 256, workspace ? workspace_bytes : (size_t)0);
+    hipStream_t hs = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    pevlm_work_item *items = (pevlm_work_item *)(ws + plan.off_items);
+    int32_t *qrow = (int32_t *)(ws + plan.off_qrow);
+    float *ml = (float *)(ws + plan.off_ml);
+    float *acc = (float *)(ws + plan.off_acc);
+    int32_t item_offset = 0, qrow_base = 0;
+    for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
+        SeqTable tab;
+        int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
+        fill_table(layout, s0, n, nullptr, &tab);
+        for (int32_t i = 0; i < n; ++i) {
+            tab.item_base[i + 1] = tab.item_base[i] + query_tiles_of_seq(tab.query[i], plan.tile_rows) * plan.num_splits;
+            tab.qrow_base[i] = qrow_base;
+            qrow_base += tab.query[i];
+        }
+        if (tab.item_base[n] > 0) {
+            hipError_t e = launch_build_query_items(tab, plan.tile_rows, plan.num_splits, (int32_t)plan.total_q,
+                                                    kKeyTile, items, item_offset, qrow, hs);
+            if (e != hipSuccess) return hip_fail(e, "query work-list builder launch");
+        }
+        item_offset += tab.item_base[n];
+    }
+    p.q = q; p.k = k; p.v = v;
+    p.part_acc = acc;
+    p.part_ml = ml;
+    p.items = items;
+    p.n_items = (int32_t)plan.n_items;
+    p.n_q_heads = heads->n_q_heads;
+    p.n_kv_heads = heads->n_kv_heads;
+    p.scale = scale_of(heads);
+    hipError_t e = heads->dtype == PEVLM_BF16 ? launch_attn_bf16(p, heads->head_dim, true, hs)
+                                              : launch_attn_f32(p, heads->head_dim, true, hs);
+    if (e != hipSuccess) return hip_fail(e, "query split launch");
+    MergeParams m;
+    m.part_acc = acc; m.part_ml = ml; m.qrow_of_compact = qrow; m.out = out; m.lse = lse;
+    m.total_q_rows = (int32_t)plan.total_q;
+    m.num_splits = plan.num_splits;
+    m.n_q_heads = heads->n_q_heads;
+    m.head_dim = heads->head_dim;
+    m.scale = p.scale;
+    m.is_bf16 = heads->dtype == PEVLM_BF16;
+    e = launch_merge(m, hs);
+    if (e != hipSuccess) return hip_fail(e, "merge launch");
+    return PEVLM_OK;
+}
+
+int64_t pevlm_prefill_worklist_host(const pevlm_layout *layout, int32_t tile_rows, pevlm_work_item *items,
+                                    int64_t capacity)
+{
+    if (check_layout(layout) != PEVLM_OK) return -1;
+    if (tile_rows < 1) { fail(PEVLM_ERR_INVALID_ARG, "tile_rows must be >= 1"); return -1; }
+    int64_t n = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        int32_t B = layout->ctx_len[s] > 0 ? layout->block_len[s] : 1;
+        int32_t cnt = prefill_items_of_seq(layout->sink_len[s], B, layout->ctx_len[s], tile_rows);
+        for (int32_t i = 0; i < cnt; ++i, ++n)
+            if (items && n < capacity)
+                items[n] = prefill_item(layout->cu_seqlens[s], layout->sink_len[s], B, layout->ctx_len[s], tile_rows, i, s);
+    }
+    return n;
+}
+
+int64_t pevlm_query_worklist_host(const pevlm_layout *layout, int32_t tile_rows, int32_t num_splits,
+                                  pevlm_work_item *items, int64_t capacity)
+{
+    if (check_layout(layout) != PEVLM_OK) return -1;
+    if (tile_rows < 1 || num_splits < 1) { fail(PEVLM_ERR_INVALID_ARG, "tile_rows and num_splits must be >= 1"); return -1; }
+    int64_t total_q = total_query_rows(layout);
+    int64_t n = 0;
+    int32_t qrow_base = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        int32_t cnt = query_tiles_of_seq(layout->query_len[s], tile_rows) * num_splits;
+        for (int32_t i = 0; i < cnt; ++i, ++n)
+            if (items && n < capacity)
+                items[n] = query_item(layout->cu_seqlens[s], layout->sink_len[s], layout->ctx_len[s], layout->query_len[s],
+                                      tile_rows, num_splits, i, s, qrow_base, (int32_t)total_q, kKeyTile);
+        qrow_base += layout->query_len[s];
+    }
+    return n;
+}
+
+pevlm_status pevlm_visible_pairs(const pevlm_layout *layout, int64_t *sink_pairs, int64_t *block_pairs,
+                                 int64_t *question_pairs)
+{
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    int64_t ps = 0, pb = 0, pq = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        int64_t S = layout->sink_len[s], C = layout->ctx_len[s], Q = layout->query_len[s];
+        int64_t B = C > 0 ? layout->block_len[s] : 1;
+        ps += S * (S + 1) / 2;
+        int64_t nfull = C / B, last = C % B;
+        pb += nfull * (B * S + B * (B + 1) / 2) + (last ? last * S + last * (last + 1) / 2 : 0);
+        pq += Q * (S + C) + Q * (Q + 1) / 2;
+    }
+    if (sink_pairs) *sink_pairs = ps;
+    if (block_pairs) *block_pairs = pb;
+    if (question_pairs) *question_pairs = pq;
+    return PEVLM_OK;
+}
+
+}  // extern "C"

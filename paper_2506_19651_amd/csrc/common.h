@@ -1,0 +1,170 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels of libpevlm.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pevlm.h"
+
+namespace pevlm {
+
+// ------------------------------------------------------------------------------------------
+// Sequence table handed to the work-list builder kernels by value (kernel argument memory), so
+// that the caller's host arrays may be released as soon as the entry point returns.
+// ------------------------------------------------------------------------------------------
+constexpr int kMaxSeqsPerLaunch = 48;
+constexpr int kMaxHeads = 256;
+
+struct SeqTable {
+    int32_t num_seqs;                          // sequences in this chunk
+    int32_t seq_index0;                        // index of the chunk's first sequence in the batch
+    int32_t start[kMaxSeqsPerLaunch];          // first packed row of the sequence
+    int32_t sink[kMaxSeqsPerLaunch];           // S
+    int32_t block[kMaxSeqsPerLaunch];          // B (>= 1)
+    int32_t ctx[kMaxSeqsPerLaunch];            // C
+    int32_t query[kMaxSeqsPerLaunch];          // Q
+    int32_t item_base[kMaxSeqsPerLaunch + 1];  // first work item of the sequence (chunk-relative)
+    int32_t qrow_base[kMaxSeqsPerLaunch];      // first compact question row of the sequence
+    int32_t pos_offset[kMaxSeqsPerLaunch];     // added to every position of the sequence (RoPE)
+};
+
+struct HeadTable {
+    uint8_t kv_of_q[kMaxHeads];     // KV head of query head h
+    uint8_t head_order[kMaxHeads];  // query heads sorted by KV head (stable): schedule order
+};
+
+// Work items of a region tiling (Sec. "Formulations": a query tile never leaves its region).
+__host__ __device__ inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+__host__ __device__ inline int32_t prefill_items_of_seq(int32_t S, int32_t B, int32_t C, int32_t tile_rows)
+{
+    int32_t n = ceil_div(S, tile_rows);
+    if (C > 0) {
+        int32_t nb = ceil_div(C, B);
+        int32_t last = C - (nb - 1) * B;
+        n += (nb - 1) * ceil_div(B, tile_rows) + ceil_div(last, tile_rows);
+    }
+    return n;
+}
+
+// idx-th prefill item of a sequence that starts at packed row `start`.
+__host__ __device__ inline pevlm_work_item prefill_item(int32_t start, int32_t S, int32_t B, int32_t C,
+                                                        int32_t tile_rows, int32_t idx, int32_t seq)
+{
+    pevlm_work_item it;
+    it.seq = seq;
+    it.reserved = 0;
+    int32_t sink_tiles = ceil_div(S, tile_rows);
+    if (idx < sink_tiles) {  // Eq. 3: sink rows see sink keys up to themselves
+        int32_t r0 = idx * tile_rows;
+        it.q_start = start + r0;
+        it.q_rows = (S - r0 < tile_rows) ? S - r0 : tile_rows;
+        it.full_start = start;
+        it.full_len = 0;
+        it.diag_start = start;
+        it.diag_len = r0 + it.q_rows;
+        return it;
+    }
+    // Eq. 4: a context block sees the whole sink and itself up to the diagonal
+    int32_t j = idx - sink_tiles;
+    int32_t tiles_per_block = ceil_div(B, tile_rows);
+    int32_t b = j / tiles_per_block, ti = j % tiles_per_block;
+    int32_t b0 = S + b * B;                       // local position of the block's first token
+    int32_t blen = (C - b * B < B) ? C - b * B : B;
+    int32_t r0 = ti * tile_rows;
+    it.q_start = start + b0 + r0;
+    it.q_rows = (blen - r0 < tile_rows) ? blen - r0 : tile_rows;
+    it.full_start = start;
+    it.full_len = S;
+    it.diag_start = start + b0;
+    it.diag_len = r0 + it.q_rows;
+    return it;
+}
+
+// Question items (Eq. 5): tiles of question rows x key splits.  The keys of a sequence
+// [start, start + L) are cut into num_splits runs of split_len keys; everything before the
+// question is visible to every question row, keys inside the question are causal.
+__host__ __device__ inline int32_t query_tiles_of_seq(int32_t Q, int32_t tile_rows) { return ceil_div(Q, tile_rows); }
+
+__host__ __device__ inline int32_t split_len_of_seq(int32_t L, int32_t num_splits, int32_t align)
+{
+    int32_t per = ceil_div(L, num_splits);
+    per = ceil_div(per, align) * align;
+    return per < align ? align : per;
+}
+
+__host__ __device__ inline pevlm_work_item query_item(int32_t start, int32_t S, int32_t C, int32_t Q,
+                                                      int32_t tile_rows, int32_t num_splits, int32_t idx,
+                                                      int32_t seq, int32_t qrow_base, int32_t total_q_rows,
+                                                      int32_t align)
+{
+    // idx = tile * num_splits + split
+    pevlm_work_item it;
+    int32_t tile = idx / num_splits, split = idx % num_splits;
+    int32_t L = S + C + Q;
+    int32_t r0 = tile * tile_rows;
+    it.seq = seq;
+    it.q_start = start + S + C + r0;
+    it.q_rows = (Q - r0 < tile_rows) ? Q - r0 : tile_rows;
+    int32_t last_key = S + C + r0 + it.q_rows;  // exclusive local bound of keys any row of the tile sees
+    int32_t sl = split_len_of_seq(L, num_splits, align);
+    int32_t lo = split * sl, hi = lo + sl;
+    if (hi > last_key) hi = last_key;
+    if (lo > hi) lo = hi;
+    int32_t qb = S + C;  // first local question position
+    int32_t full_hi = hi < qb ? hi : qb;
+    int32_t full_lo = lo < full_hi ? lo : full_hi;
+    it.full_start = start + full_lo;
+    it.full_len = full_hi - full_lo;
+    int32_t diag_lo = lo > qb ? lo : qb;
+    if (diag_lo > hi) diag_lo = hi;
+    it.diag_start = start + diag_lo;
+    it.diag_len = hi - diag_lo;
+    it.reserved = split * total_q_rows + qrow_base + r0;  // row of this tile in the partial buffers
+    return it;
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel parameter blocks
+// ------------------------------------------------------------------------------------------
+struct AttnParams {
+    const void *q, *k, *v;
+    void *out;                      // final mode: [T][Hq][D] storage type
+    float *lse;                     // final mode: [T][Hq] or nullptr
+    float *part_acc;                // partial mode: [slots][Hq][D] unnormalised weighted values
+    float *part_ml;                 // partial mode: [slots][Hq][2] (running max of raw scores, sum)
+    const pevlm_work_item *items;
+    int32_t n_items;
+    int32_t n_q_heads, n_kv_heads;
+    float scale;                    // softmax scale
+    HeadTable heads;
+};
+
+struct MergeParams {
+    const float *part_acc, *part_ml;
+    const int32_t *qrow_of_compact;  // [total_q_rows] packed row of each compact question row
+    void *out;
+    float *lse;
+    int32_t total_q_rows, num_splits, n_q_heads, head_dim;
+    float scale;
+    int32_t is_bf16;
+};
+
+// ------------------------------------------------------------------------------------------
+// Launchers implemented in the kernel translation units (all enqueue on `stream`, never sync)
+// ------------------------------------------------------------------------------------------
+hipError_t launch_build_prefill_items(const SeqTable &tab, int32_t tile_rows, pevlm_work_item *items,
+                                      int32_t item_offset, hipStream_t stream);
+hipError_t launch_build_query_items(const SeqTable &tab, int32_t tile_rows, int32_t num_splits,
+                                    int32_t total_q_rows, int32_t align, pevlm_work_item *items,
+                                    int32_t item_offset, int32_t *qrow_of_compact, hipStream_t stream);
+hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
+                       double rope_base, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
+hipError_t launch_merge(const MergeParams &p, hipStream_t stream);
+
+constexpr int32_t kTileRowsF32 = 16;   // query rows per work item of the fp32 kernels
+constexpr int32_t kTileRowsBf16 = 128; // query rows per work item of the bf16 MFMA kernels
+constexpr int32_t kKeyTile = 64;       // keys staged per step by the bf16 kernels
+
+}  // namespace pevlm

@@ -1,0 +1,163 @@
+"""Host-side logic of libpevlm that needs no GPU: exported symbols, argument validation, the
+tile work lists (expanded back to a boolean mask and compared with the oracle's explicit mask),
+and the closed-form pair counts."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_19651_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load_library()
+    header = open(os.path.join(ROOT, "include", "pevlm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(pevlm_[a-z_0-9]+)\s*\(", header))
+    assert {"pevlm_rope_seq", "pevlm_block_prefill_attn", "pevlm_query_attn"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in include/pevlm.h but not exported"
+    assert P.pevlm_version() >= 100
+
+
+LAYOUTS = [
+    [(0, 1, 0, 1)],
+    [(3, 2, 6, 4)],
+    [(1, 5, 13, 0)],
+    [(0, 2, 6, 1)],
+    [(4, 5, 0, 4)],
+    [(300, 392, 1000, 70)],
+    [(256, 128, 1024, 64)],
+    [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)],
+]
+
+
+def expand_items(items, T):
+    M = np.zeros((T, T), np.uint8)
+    owner = np.zeros(T, np.int32)
+    for it in items:
+        assert it.q_rows >= 1
+        for r in range(it.q_start, it.q_start + it.q_rows):
+            owner[r] += 1
+            M[r, it.full_start:it.full_start + it.full_len] += 1
+            hi = min(it.diag_start + it.diag_len, r + 1)
+            if hi > it.diag_start:
+                M[r, it.diag_start:hi] += 1
+    return M, owner
+
+
+@pytest.mark.parametrize("seqs", LAYOUTS)
+@pytest.mark.parametrize("tile_rows", [1, 16, 128])
+def test_prefill_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows):
+    lay = P.Layout.from_seqs(seqs)
+    T = lay.total_tokens
+    olay = oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q)
+    want = oracle.mask_matrix(olay)
+    items = P.pevlm_prefill_worklist_host(lay, tile_rows)
+    got, owner = expand_items(items, T)
+    is_question = np.zeros(T, bool)
+    for si, (S, B, C, Q) in enumerate(seqs):
+        is_question[lay.cu[si] + S + C: lay.cu[si + 1]] = True
+    assert np.all(owner[~is_question] == 1) and np.all(owner[is_question] == 0)  # each row exactly once
+    assert np.array_equal(got[~is_question], want[~is_question])                 # and exactly its keys, once
+    for it in items:  # a tile never leaves its region and never exceeds the tile size
+        assert it.q_rows <= tile_rows
+    n_expected = 0
+    for (S, B, C, Q) in seqs:
+        n_expected += -(-S // tile_rows)
+        nb = -(-C // B) if C else 0
+        for b in range(nb):
+            n_expected += -(-min(B, C - b * B) // tile_rows)
+    assert len(items) == n_expected
+
+
+@pytest.mark.parametrize("seqs", LAYOUTS)
+@pytest.mark.parametrize("tile_rows,num_splits", [(16, 1), (16, 3), (128, 4), (128, 64), (1, 2)])
+def test_query_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows, num_splits):
+    lay = P.Layout.from_seqs(seqs)
+    T = lay.total_tokens
+    olay = oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q)
+    want = oracle.mask_matrix(olay)
+    items = P.pevlm_query_worklist_host(lay, tile_rows, num_splits)
+    got, owner = expand_items(items, T)
+    total_q = sum(q for (_, _, _, q) in seqs)
+    slots = set()
+    for it in items:  # every (split, question row) owns a distinct slot of the partial buffers
+        for r in range(it.q_rows):
+            slot = it.reserved + r
+            assert 0 <= slot < num_splits * total_q and slot not in slots
+            slots.add(slot)
+    assert len(slots) == num_splits * total_q
+    for si, (S, B, C, Q) in enumerate(seqs):
+        lo, hi = lay.cu[si] + S + C, lay.cu[si + 1]
+        assert np.all(owner[lo:hi] == num_splits)
+        assert np.array_equal(got[lo:hi], want[lo:hi])  # splits partition each row's keys exactly
+        assert np.all(got[lay.cu[si]:lo] == 0)
+
+
+def test_visible_pairs_match_oracle_mask_and_golden(oracle):
+    for seqs in LAYOUTS:
+        lay = P.Layout.from_seqs(seqs)
+        olay = oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q)
+        M = oracle.mask_matrix(olay)
+        sums = [0, 0, 0]
+        for si, (S, B, C, Q) in enumerate(seqs):
+            b = lay.cu[si]
+            sums[0] += int(M[b:b + S].sum())
+            sums[1] += int(M[b + S:b + S + C].sum())
+            sums[2] += int(M[b + S + C:b + S + C + Q].sum())
+        assert P.pevlm_visible_pairs(lay) == tuple(sums)
+    golden = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "pair_counts.txt")):
+        if line.strip() and not line.startswith("#"):
+            n, a, b, c = line.split()
+            golden[n] = (int(a), int(b), int(c))
+    import workloads as W
+    for name, want in golden.items():
+        w = W.CONFIGS[name]
+        assert P.pevlm_visible_pairs(P.Layout.from_seqs(w.seqs)) == want
+    # headline config: useful FLOPs of the block-prefill path
+    w = W.CONFIGS["c3"]
+    pre, que = P.useful_flops(P.Layout.from_seqs(w.seqs), P.Heads(28, 4, 128, "bf16"))
+    assert pre == 4 * 128 * 28 * (32896 + 50364416) and que == 4 * 128 * 28 * 8429632
+
+
+def test_argument_validation_without_gpu():
+    """Invalid arguments are rejected before anything touches the device."""
+    lib = P.load_library()
+    lay = P.Layout.from_seqs([(3, 2, 6, 4)])
+    heads = P.Heads(4, 2, 64, "f32")
+    fake = ctypes.c_void_p(0x1000)  # aligned, never dereferenced on these paths
+    call = lambda l, h, q=fake: lib.pevlm_block_prefill_attn(q, fake, fake, fake, None, l.ref(), h.ref(), None, 0, None)
+    bad_sum = P.Layout([0, 10], [3], [2], [6], [4])
+    assert call(bad_sum, heads) == P.binding.PEVLM_ERR_INVALID_ARG and "sink+ctx+query" in P.pevlm_last_error()
+    assert call(P.Layout([0, 13], [3], [0], [6], [4]), heads) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(P.Layout([0, 5], [-1], [2], [2], [4]), heads) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(lay, P.Heads(4, 3, 64, "f32")) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(lay, P.Heads(4, 2, 64, "f32", kv_head_of_q=[0, 1, 2, 0])) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(lay, P.Heads(4, 2, 96, "f32")) == P.binding.PEVLM_ERR_UNSUPPORTED
+    assert call(lay, P.Heads(4, 2, 64, 7)) == P.binding.PEVLM_ERR_UNSUPPORTED
+    assert call(lay, heads, None) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(lay, heads, ctypes.c_void_p(0x1004)) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert call(lay, heads) == P.binding.PEVLM_ERR_WORKSPACE_TOO_SMALL
+    assert "workspace" in P.pevlm_last_error()
+    q = lambda ns: lib.pevlm_query_attn(fake, fake, fake, fake, None, lay.ref(), heads.ref(), ns, None, 0, None)
+    assert q(-1) == P.binding.PEVLM_ERR_INVALID_ARG and q(65) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert q(0) == P.binding.PEVLM_ERR_WORKSPACE_TOO_SMALL
+    assert lib.pevlm_rope_seq(fake, fake, lay.ref(), heads.ref(), -1.0, None, None) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert P.pevlm_block_prefill_workspace_bytes(bad_sum, heads) == 0
+    assert P.pevlm_query_workspace_bytes(lay, heads, 0) > 0
+
+
+def test_workspace_sizes_cover_items_and_partials():
+    lay = P.Layout.from_seqs([(256, 1024, 65536, 128)])
+    heads = P.Heads(28, 4, 128, "bf16")
+    n = len(P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows()))
+    assert P.pevlm_block_prefill_workspace_bytes(lay, heads) >= n * ctypes.sizeof(P.WorkItem)
+    for ns in (1, 8, 64):
+        need = ns * 128 * 28 * (128 + 2) * 4 + 128 * 4 + ns * ctypes.sizeof(P.WorkItem)
+        assert P.pevlm_query_workspace_bytes(lay, heads, ns) >= need

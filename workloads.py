@@ -96,10 +96,19 @@ def small_variant(w: Workload, name: str, seqs, **kw) -> Workload:
 
 # ----------------------------------------------------------------------------- storage rounding
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """Round-to-nearest-even float32 -> bf16 bit patterns (uint16)."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
-    return (rounded >> np.uint32(16)).astype(np.uint16)
+    """Round-to-nearest-even float32 -> bf16 bit patterns (uint16), in slabs to bound temporaries."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    xf, of = x.reshape(-1), out.reshape(-1)
+    step = 1 << 22
+    for lo in range(0, xf.size, step):
+        u = xf[lo:lo + step].view(np.uint32)
+        r = (u >> np.uint32(16)) & np.uint32(1)
+        r += np.uint32(0x7FFF)
+        r += u
+        r >>= np.uint32(16)
+        of[lo:lo + step] = r
+    return out
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
