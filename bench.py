@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the PEVLM prefill attention path on one MI355X.
+
+A step is one pass of the whole hot path over the 64K-token workload (c3): sequential RoPE of Q and
+K, block-parallel prefill attention (sink + 64 context blocks), split-KV question attention + merge.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line:
+  value      useful TFLOP/s of the whole path (only unmasked FLOPs: 4*D per visible pair per head)
+  roofline   the dominant kernel (block-prefill attention) against the bf16 MFMA peak, its duration
+             measured with HIP events on the launch stream inside the timed region
+  cpu_baseline  the fp64 CPU oracle timed on a bounded row sample of the same workload
+and, as context, ms per kernel, this build's own dense full-causal attention on the same tokens and
+the resulting attention speedup (the paper reports up to 7.47x on one H20-96G).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-causal", action="store_true")
+    ap.add_argument("--num-splits", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this path uses no collectives and every GPU box here has one "
+              "GPU; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2506_19651_amd as P
+    import workloads as W
+
+    if not os.path.exists(P.lib_path()):
+        from paper_2506_19651_amd.build import build_library
+        build_library()
+    P.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = W.CONFIGS[args.workload]
+    assert w.dtype == "bf16"
+    data = W.generate(w)
+
+    def to_dev(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    lay = P.Layout.from_seqs(w.seqs)
+    heads = P.Heads(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    q0, k0, v = to_dev(data["q"]), to_dev(data["k"]), to_dev(data["v"])
+    q, k = q0.clone(), k0.clone()
+    out = torch.zeros_like(q)
+    ws_p = torch.empty(P.pevlm_block_prefill_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
+    ws_q = torch.empty(P.pevlm_query_workspace_bytes(lay, heads, args.num_splits), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        P.pevlm_rope_seq(q, k, lay, heads, w.rope_base, stream=stream)
+        if ev:
+            ev[1].record(stream)
+        P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, workspace=ws_p, stream=stream)
+        if ev:
+            ev[2].record(stream)
+        P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=args.num_splits, workspace=ws_q, stream=stream)
+        if ev:
+            ev[3].record(stream)
+
+    # first pass on the pristine inputs: kept for the accuracy figures reported next to the timing
+    step()
+    torch.cuda.synchronize()
+    first_out = out.clone()
+
+    for _ in range(args.warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_rope = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_prefill = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    ms_query = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+
+    f_prefill, f_query = P.useful_flops(lay, heads)
+    T = w.total_tokens
+    rope_bytes = 2 * T * (w.n_q_heads + w.n_kv_heads) * w.head_dim * 2
+    kv_bytes = 2 * T * w.n_kv_heads * w.head_dim * 2
+
+    result = {
+        "metric": "pevlm_prefill_attention_useful_tflops",
+        "value": round((f_prefill + f_query) / (ms_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: sink {w.seqs[0][0]}, {w.seqs[0][2] // w.seqs[0][1]} blocks x {w.seqs[0][1]}, "
+                               f"question {w.seqs[0][3]}, L={T}, {w.n_q_heads}/{w.n_kv_heads} heads x {w.head_dim}",
+                   "tokens": T, "num_splits": args.num_splits},
+        "ms_per_layer": round(ms_rope + ms_prefill + ms_query, 4),
+        "ms_rope": round(ms_rope, 4),
+        "ms_block_prefill": round(ms_prefill, 4),
+        "ms_query_attn": round(ms_query, 4),
+        "block_prefill_useful_tflops": round(f_prefill / (ms_prefill * 1e-3) / 1e12, 2),
+        "query_attn_useful_tflops": round(f_query / (ms_query * 1e-3) / 1e12, 2),
+        "rope_gbs": round(rope_bytes / (ms_rope * 1e-3) / 1e9, 1),
+        "query_kv_gbs": round(kv_bytes / (ms_query * 1e-3) / 1e9, 1),
+        "roofline": {
+            "kernel": "attn_bf16_kernel<128,false> (block-prefill)",
+            "bound": "mfma",
+            "achieved": round(f_prefill / (ms_prefill * 1e-3) / 1e12, 2),
+            "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(f_prefill / (ms_prefill * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+        },
+        "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
+    }
+
+    if not args.no_full_causal:
+        wf = W.CONFIGS["c3_full_causal"] if args.workload == "c3" else W.small_variant(
+            w, w.name + "_full_causal", [(0, s + c + qq, s + c + qq, 0) for (s, b, c, qq) in w.seqs])
+        layf = P.Layout.from_seqs(wf.seqs)
+        ws_f = torch.empty(P.pevlm_block_prefill_workspace_bytes(layf, heads), dtype=torch.uint8, device=dev)
+        outf = torch.empty_like(q)
+        P.pevlm_block_prefill_attn(q, k, v, outf, layf, heads, workspace=ws_f, stream=stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record(stream)
+        for _ in range(reps):
+            P.pevlm_block_prefill_attn(q, k, v, outf, layf, heads, workspace=ws_f, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms_full = e0.elapsed_time(e1) / reps
+        ff, _ = P.useful_flops(layf, heads)
+        result["ms_full_causal"] = round(ms_full, 3)
+        result["full_causal_useful_tflops"] = round(ff / (ms_full * 1e-3) / 1e12, 2)
+        result["attn_speedup_vs_full_causal"] = round(ms_full / (ms_prefill + ms_query), 2)
+        del outf
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        a = w.layout_arrays()
+        olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"])
+        rows = W.sample_rows(w, n_random=256, max_question_rows=24)
+        pairs = int(sum(int(oracle.mask_row(olay, int(t)).sum()) for t in rows))
+        tc0 = time.perf_counter()
+        want, _ = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=rows)
+        tc1 = time.perf_counter()
+        cpu_flops = 4 * w.head_dim * w.n_q_heads * pairs
+        got = first_out[torch.from_numpy(rows).to(dev)].float().cpu().numpy()
+        err = np.abs(got - want)
+        result["cpu_baseline"] = {
+            "value": round(cpu_flops / (tc1 - tc0) / 1e12, 6),
+            "unit": "TFLOP/s",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"{len(rows)} of {T} rows of {w.name} (region/block/tile edges, 24 question rows, 256 seeded "
+                      f"random rows) x all heads, {pairs} visible pairs/head, {tc1 - tc0:.1f} s incl. fp64 RoPE of all keys",
+        }
+        result["max_abs_err_vs_oracle"] = float(err.max())
+        result["mean_abs_err_vs_oracle"] = float(err.mean())
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

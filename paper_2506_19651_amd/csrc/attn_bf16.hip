@@ -33,8 +33,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     constexpr int KSTEPS = D / 16;        // MFMA k-steps of Q K^T
     constexpr int DBLK = D / 32;          // 32-wide blocks of head_dim in O^T
     constexpr int VSW = CH / 4 - 1;       // V swizzle mask (64-byte granules per row - 1)
-    __shared__ __attribute__((aligned(16))) uint8_t lds_k[KT * ROWB];
-    __shared__ __attribute__((aligned(16))) uint8_t lds_v[KT * ROWB];
+    constexpr int TILEB = KT * ROWB;      // bytes of one staged K (or V) tile
+    constexpr int RPI = 1024 / ROWB;      // rows one wavefront-wide 16-byte-per-lane load covers
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_k[2 * TILEB];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_v[2 * TILEB];
 
     // Workgroup -> logical id.  Consecutive workgroup ids land on different XCDs (8 of them, each
     // with its own L2); give every XCD one contiguous run of logical ids so that the heads of a GQA
@@ -80,50 +82,55 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     const int32_t n_full_tiles = (it.full_len + KT - 1) / KT;
     const int32_t n_tiles = n_full_tiles + (it.diag_len + KT - 1) / KT;
 
-    // ---- global -> register prefetch of one K/V tile (rows past the range repeat its last key) ----
-    uint4 kreg[NLD], vreg[NLD];
-    auto tile_range = [&](int32_t t, int32_t &k0, int32_t &kend, bool &causal) {
-        if (t < n_full_tiles) {
-            k0 = it.full_start + t * KT;
-            kend = it.full_start + it.full_len;
-            causal = false;
-        } else {
-            k0 = it.diag_start + (t - n_full_tiles) * KT;
-            kend = it.diag_start + it.diag_len;
-            causal = true;
-        }
-    };
-    auto prefetch = [&](int32_t t) {
-        int32_t k0, kend;
-        bool causal;
-        tile_range(t, k0, kend, causal);
-#pragma unroll
-        for (int r = 0; r < NLD; ++r) {
-            const int32_t c = tid + 256 * r;
-            const int32_t row = c / CH, ch = c % CH;
-            int32_t key = k0 + row;
-            key = key < kend ? key : kend - 1;
-            const int64_t off = ((int64_t)key * Hkv + g) * D + ch * 8;
-            kreg[r] = *reinterpret_cast<const uint4 *>(K + off);
-            vreg[r] = *reinterpret_cast<const uint4 *>(V + off);
-        }
-    };
+    // ---- K/V tiles go straight from global memory into LDS (global_load_lds, 16 bytes per lane): a
+    // wavefront instruction fills 1 KB of contiguous LDS, i.e. RPI whole rows; the XOR swizzle is
+    // applied by choosing which 16-byte chunk of the row each lane fetches.  Two LDS stages: tile
+    // t+1 streams in while tile t is consumed.  Rows past the key range repeat its last key (their
+    // scores are masked, their values stay finite).
+#define PEVLM_TILE_RANGE(t, k0, kend, causal)                 \
+    do {                                                      \
+        if ((t) < n_full_tiles) {                             \
+            k0 = it.full_start + (t) * KT;                    \
+            kend = it.full_start + it.full_len;               \
+            causal = false;                                   \
+        } else {                                              \
+            k0 = it.diag_start + ((t) - n_full_tiles) * KT;   \
+            kend = it.diag_start + it.diag_len;               \
+            causal = true;                                    \
+        }                                                     \
+    } while (0)
+#define PEVLM_ISSUE_TILE(t, stage)                                                                        \
+    do {                                                                                                  \
+        int32_t pk0, pkend;                                                                               \
+        bool pcausal;                                                                                     \
+        PEVLM_TILE_RANGE(t, pk0, pkend, pcausal);                                                         \
+        (void)pcausal;                                                                                    \
+        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                                 \
+            const int32_t rbase = (j * 4 + wave) * RPI;                                                   \
+            const int32_t row = rbase + lane / CH, cpos = lane % CH;                                      \
+            int32_t key = pk0 + row;                                                                      \
+            key = key < pkend ? key : pkend - 1;                                                          \
+            const int64_t roff = ((int64_t)key * Hkv + g) * D;                                            \
+            const uint16_t *ksrc = K + roff + ((cpos ^ (row & (CH - 1))) << 3);                           \
+            const uint16_t *vsrc = V + roff + ((cpos ^ ((row & VSW) << 2)) << 3);                         \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ksrc,        \
+                                             LDS_PTR(void, lds_k + (stage) * TILEB + rbase * ROWB), 16, 0, 0); \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)vsrc,        \
+                                             LDS_PTR(void, lds_v + (stage) * TILEB + rbase * ROWB), 16, 0, 0); \
+        }                                                                                                 \
+    } while (0)
 
-    if (n_tiles > 0) prefetch(0);
+    if (n_tiles > 0) PEVLM_ISSUE_TILE(0, 0);
     for (int32_t t = 0; t < n_tiles; ++t) {
-        __syncthreads();  // every wave is done reading the previous tile
-#pragma unroll
-        for (int r = 0; r < NLD; ++r) {
-            const int32_t c = tid + 256 * r;
-            const int32_t row = c / CH, ch = c % CH;
-            *reinterpret_cast<uint4 *>(lds_k + row * ROWB + ((ch ^ (row & (CH - 1))) << 4)) = kreg[r];
-            *reinterpret_cast<uint4 *>(lds_v + row * ROWB + ((ch ^ ((row & VSW) << 2)) << 4)) = vreg[r];
-        }
-        __syncthreads();
+        const int32_t stage = t & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of tile t has landed in LDS
+        __syncthreads();                     // ... and everyone's; all waves are done with tile t-1
+        if (t + 1 < n_tiles) PEVLM_ISSUE_TILE(t + 1, stage ^ 1);
+        const uint8_t *tk = lds_k + stage * TILEB;
+        const uint8_t *tv = lds_v + stage * TILEB;
         int32_t k0, kend;
         bool causal;
-        tile_range(t, k0, kend, causal);
-        if (t + 1 < n_tiles) prefetch(t + 1);  // in flight while this tile is computed
+        PEVLM_TILE_RANGE(t, k0, kend, causal);
 
         // keys of this tile the wave needs, in 32-key chunks
         int32_t lim = kend - k0;
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
 #pragma unroll
                 for (int kk = 0; kk < KSTEPS; ++kk) {
                     const int32_t ch = kk * 2 + g32;
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds_k + row * ROWB + ((ch ^ (row & (CH - 1))) << 4));
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(tk + row * ROWB + ((ch ^ (row & (CH - 1))) << 4));
                     s[kc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[kc], 0, 0, 0);
                 }
             }
@@ -185,10 +192,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
                 }
             }
         l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.f)) {  // the running maximum of some row moved: rescale the accumulators
 #pragma unroll
-        for (int b = 0; b < DBLK; ++b)
+            for (int b = 0; b < DBLK; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+                for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+        }
 
         // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -202,7 +211,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
                         const int32_t row = ks * 16 + tt * 8 + g32 * 4 + ((lane & 15) >> 2);
                         const int32_t dcol = b * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
                         const int32_t ch = dcol >> 3;
-                        const uint8_t *ptr = lds_v + row * ROWB + ((ch ^ ((row & VSW) << 2)) << 4) + (dcol & 7) * 2;
+                        const uint8_t *ptr = tv + row * ROWB + ((ch ^ ((row & VSW) << 2)) << 4) + (dcol & 7) * 2;
                         const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));
                         const bf16x4 rb = __builtin_bit_cast(bf16x4, r);
                         a[tt * 4 + 0] = rb[0]; a[tt * 4 + 1] = rb[1]; a[tt * 4 + 2] = rb[2]; a[tt * 4 + 3] = rb[3];
