@@ -39,6 +39,22 @@ __device__ __forceinline__ float max3f(float a, float b, float c)
     return r;
 }
 
+// Same, with a wavefront-uniform 64-bit base address and a per-lane 32-bit byte offset.
+__device__ __forceinline__ void load_lds_16_base(const void *sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
+// Marks a pointer that is the same in every lane as wavefront-uniform (scalar registers).
+template <typename T>
+__device__ __forceinline__ const T *uniform_ptr(const T *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const T *)(((uint64_t)hi << 32) | lo);
+}
+
 template <int D>
 struct TileCfg {
     static constexpr int KT = kKeyTile;        // keys per staged tile
@@ -80,25 +96,41 @@ __device__ __forceinline__ void process_tile(const uint8_t *tk, const uint8_t *t
         for (int i = 0; i < 16; ++i) s[kc][i] = 0.f;
 
     // ---- S^T = K Q^T: A fragments (16 bytes per lane) are fetched one chunk ahead of the MFMAs ----
+    // The two 32-key chunks form two independent accumulation chains that are issued alternately.
     bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
+    constexpr int HK = C::KSTEPS / 2;
 #pragma unroll
-    for (int kk = 0; kk < C::KSTEPS; ++kk)
+    for (int kk = 0; kk < HK; ++kk) {
         a0[kk] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + (((kk * 2 + g32) ^ k_swz) << 4));
+        a1[kk] = *reinterpret_cast<const bf16x8 *>(tk + 32 * C::ROWB + k_row_off + (((kk * 2 + g32) ^ k_swz) << 4));
+    }
     __builtin_amdgcn_sched_barrier(0);
     if (nkc > 1) {
 #pragma unroll
-        for (int kk = 0; kk < C::KSTEPS; ++kk) {
+        for (int kk = 0; kk < HK; ++kk) {
             s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-            a1[kk] = *reinterpret_cast<const bf16x8 *>(tk + 32 * C::ROWB + k_row_off + (((kk * 2 + g32) ^ k_swz) << 4));
+            a0[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
+            a1[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + 32 * C::ROWB + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < C::KSTEPS; ++kk) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
+        for (int kk = HK; kk < C::KSTEPS; ++kk) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
+        }
     } else {
 #pragma unroll
-        for (int kk = 0; kk < C::KSTEPS; ++kk) s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
+        for (int kk = 0; kk < HK; ++kk) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
+            a0[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
+        }
+#pragma unroll
+        for (int kk = HK; kk < C::KSTEPS; ++kk) s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
     }
 
     // ---- V^T fragments of the first 16 keys: in flight during the softmax ----
@@ -266,21 +298,40 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             causal = true;                                    \
         }                                                     \
     } while (0)
+    // Per-lane byte offsets of the NLD loads inside a tile are fixed (row within the tile, swizzled
+    // chunk); a tile that lies wholly inside its key range only needs a new uniform base address.
+    uint32_t koff[NLD], voff[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int32_t row = (j * 4 + wave) * RPI + lane / CH, cpos = lane % CH;
+        koff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ (row & (CH - 1))) << 3)) * 2);
+        voff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ ((row & VSW) << 2)) << 3)) * 2);
+    }
 #define PEVLM_ISSUE_TILE(t, stage)                                                                   \
     do {                                                                                             \
         int32_t pk0, pkend;                                                                          \
         bool pcausal;                                                                                \
         PEVLM_TILE_RANGE(t, pk0, pkend, pcausal);                                                    \
         (void)pcausal;                                                                               \
-        _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                            \
-            const int32_t rbase = (j * 4 + wave) * RPI;                                              \
-            const int32_t row = rbase + lane / CH, cpos = lane % CH;                                 \
-            int32_t key = pk0 + row;                                                                 \
-            key = key < pkend ? key : pkend - 1;                                                     \
-            const int64_t roff = ((int64_t)key * Hkv + g) * D;                                       \
-            const uint32_t dst = (uint32_t)((stage) * TILEB + rbase * ROWB);                         \
-            load_lds_16(K + roff + ((cpos ^ (row & (CH - 1))) << 3), lds_k_addr + dst);              \
-            load_lds_16(V + roff + ((cpos ^ ((row & VSW) << 2)) << 3), lds_v_addr + dst);            \
+        if (pk0 + KT <= pkend) {                                                                     \
+            const uint16_t *kb = uniform_ptr(K + ((int64_t)pk0 * Hkv + g) * D);                      \
+            const uint16_t *vb = uniform_ptr(V + ((int64_t)pk0 * Hkv + g) * D);                      \
+            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                        \
+                const uint32_t dst = (uint32_t)((stage) * TILEB + (j * 4 + wave) * RPI * ROWB);      \
+                load_lds_16_base(kb, koff[j], lds_k_addr + dst);                                     \
+                load_lds_16_base(vb, voff[j], lds_v_addr + dst);                                     \
+            }                                                                                        \
+        } else {                                                                                     \
+            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                        \
+                const int32_t rbase = (j * 4 + wave) * RPI;                                          \
+                const int32_t row = rbase + lane / CH, cpos = lane % CH;                             \
+                int32_t key = pk0 + row;                                                             \
+                key = key < pkend ? key : pkend - 1;                                                 \
+                const int64_t roff = ((int64_t)key * Hkv + g) * D;                                   \
+                const uint32_t dst = (uint32_t)((stage) * TILEB + rbase * ROWB);                     \
+                load_lds_16(K + roff + ((cpos ^ (row & (CH - 1))) << 3), lds_k_addr + dst);          \
+                load_lds_16(V + roff + ((cpos ^ ((row & VSW) << 2)) << 3), lds_v_addr + dst);        \
+            }                                                                                        \
         }                                                                                            \
     } while (0)
 
