@@ -167,7 +167,7 @@ def main():
         oracle.build()
         a = w.layout_arrays()
         olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"])
-        rows = W.sample_rows(w, n_random=256, max_question_rows=24)
+        rows = W.sample_rows(w, n_random=8192)
         pairs = int(sum(int(oracle.mask_row(olay, int(t)).sum()) for t in rows))
         tc0 = time.perf_counter()
         want, _ = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=rows)
@@ -180,7 +180,7 @@ def main():
             "unit": "TFLOP/s",
             "cores": oracle.threads(),
             "kind": "oracle",
-            "sample": f"{len(rows)} of {T} rows of {w.name} (region/block/tile edges, 24 question rows, 256 seeded "
+            "sample": f"{len(rows)} of {T} rows of {w.name} (region/block/tile edges, all question rows, 8192 seeded "
                       f"random rows) x all heads, {pairs} visible pairs/head, {tc1 - tc0:.1f} s incl. fp64 RoPE of all keys",
         }
         result["max_abs_err_vs_oracle"] = float(err.max())

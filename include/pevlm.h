@@ -131,13 +131,19 @@ typedef struct {
     int32_t seq, reserved;
 } pevlm_work_item;
 
-/* Rows per query tile used by the bf16 block-prefill kernel. */
-int32_t pevlm_prefill_tile_rows(void);
+/* Query rows per work item the kernels selected by `heads` use for the block-prefill call and for
+ * the question call (-1 for an invalid descriptor). */
+int32_t pevlm_prefill_tile_rows(const pevlm_heads *heads);
+int32_t pevlm_query_tile_rows(const pevlm_heads *heads);
 /* Enumerates, on the host, exactly the work list the device builder writes.  Returns the number
  * of items (also when items == NULL or capacity is too small: then nothing beyond capacity is
  * written), or -1 for an invalid layout. */
 int64_t pevlm_prefill_worklist_host(const pevlm_layout *layout, int32_t tile_rows,
                                     pevlm_work_item *items, int64_t capacity);
+/* Same for the question call: tiles of question rows x num_splits key runs; `reserved` holds the
+ * first row of the item in the partial buffers. */
+int64_t pevlm_query_worklist_host(const pevlm_layout *layout, int32_t tile_rows, int32_t num_splits,
+                                  pevlm_work_item *items, int64_t capacity);
 /* Visible (query, key) pairs per head implied by the layout, split by region; the causal closed
  * forms behind the paper's operation counts (Eq. 6-10).  Any output pointer may be NULL.
  * Returns PEVLM_OK or PEVLM_ERR_INVALID_ARG. */

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     pevlm_prefill_tile_rows,
     pevlm_prefill_worklist_host,
     pevlm_query_attn,
+    pevlm_query_tile_rows,
     pevlm_query_workspace_bytes,
     pevlm_query_worklist_host,
     pevlm_rope_seq,

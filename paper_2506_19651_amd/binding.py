@@ -71,6 +71,9 @@ def load_library():
         lib.pevlm_last_error.restype = ctypes.c_char_p
         lib.pevlm_version.restype = i32
         lib.pevlm_prefill_tile_rows.restype = i32
+        lib.pevlm_prefill_tile_rows.argtypes = [HP]
+        lib.pevlm_query_tile_rows.restype = i32
+        lib.pevlm_query_tile_rows.argtypes = [HP]
         lib.pevlm_prefill_worklist_host.restype = ctypes.c_int64
         lib.pevlm_prefill_worklist_host.argtypes = [LP, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_query_worklist_host.restype = ctypes.c_int64
@@ -159,8 +162,12 @@ def pevlm_version() -> int:
     return int(load_library().pevlm_version())
 
 
-def pevlm_prefill_tile_rows() -> int:
-    return int(load_library().pevlm_prefill_tile_rows())
+def pevlm_prefill_tile_rows(heads: "Heads") -> int:
+    return int(load_library().pevlm_prefill_tile_rows(heads.ref()))
+
+
+def pevlm_query_tile_rows(heads: "Heads") -> int:
+    return int(load_library().pevlm_query_tile_rows(heads.ref()))
 
 
 def pevlm_rope_seq(q, k, layout: Layout, heads: Heads, rope_base: float, pos_offset=None, stream=None):

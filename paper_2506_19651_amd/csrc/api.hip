@@ -80,7 +80,10 @@ static float scale_of(const pevlm_heads *h)
     return h->softmax_scale > 0.f ? h->softmax_scale : (float)(1.0 / sqrt((double)h->head_dim));
 }
 
-static int32_t tile_rows_of(const pevlm_heads *h) { return h->dtype == PEVLM_BF16 ? kTileRowsBf16 : kTileRowsF32; }
+static int32_t tile_rows_of(const pevlm_heads *h, bool /*query*/)
+{
+    return h->dtype == PEVLM_BF16 ? kTileRowsBf16 : kTileRowsF32;
+}
 
 // Fills the chunk table for sequences [s0, s0 + n).
 static void fill_table(const pevlm_layout *lay, int32_t s0, int32_t n, const int32_t *pos_offset, SeqTable *t)
@@ -125,7 +128,7 @@ static int64_t total_query_rows(const pevlm_layout *lay)
 // times, but no split shorter than a few key tiles.
 static int32_t auto_splits(const pevlm_layout *lay, const pevlm_heads *h)
 {
-    int64_t tiles = count_query_tiles(lay, tile_rows_of(h));
+    int64_t tiles = count_query_tiles(lay, tile_rows_of(h, true));
     if (tiles == 0) return 1;
     int64_t max_len = 0;
     for (int32_t s = 0; s < lay->num_seqs; ++s)
@@ -144,7 +147,7 @@ struct QueryPlan {
 static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits)
 {
     QueryPlan p;
-    p.tile_rows = tile_rows_of(h);
+    p.tile_rows = tile_rows_of(h, true);
     p.num_splits = num_splits > 0 ? num_splits : auto_splits(lay, h);
     p.total_q = total_query_rows(lay);
     p.n_items = count_query_tiles(lay, p.tile_rows) * p.num_splits;
@@ -169,7 +172,8 @@ extern "C" {
 
 const char *pevlm_last_error(void) { return g_err; }
 int32_t pevlm_version(void) { return 100; }
-int32_t pevlm_prefill_tile_rows(void) { return kTileRowsBf16; }
+int32_t pevlm_prefill_tile_rows(const pevlm_heads *heads) { return check_heads(heads, nullptr) == PEVLM_OK ? tile_rows_of(heads, false) : -1; }
+int32_t pevlm_query_tile_rows(const pevlm_heads *heads) { return check_heads(heads, nullptr) == PEVLM_OK ? tile_rows_of(heads, true) : -1; }
 
 pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const pevlm_heads *heads,
                             double rope_base, const int32_t *pos_offset, void *stream)
@@ -194,7 +198,7 @@ pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const 
 size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
 {
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
-    return align256((size_t)count_prefill_items(layout, tile_rows_of(heads)) * sizeof(pevlm_work_item)) + 256;
+    return align256((size_t)count_prefill_items(layout, tile_rows_of(heads, false)) * sizeof(pevlm_work_item)) + 256;
 }
 
 pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *v, void *out, float *lse,
@@ -210,7 +214,7 @@ pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *
     if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
         return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    int32_t tile_rows = tile_rows_of(heads);
+    int32_t tile_rows = tile_rows_of(heads, false);
     int64_t n_items = count_prefill_items(layout, tile_rows);
     if (n_items == 0) return PEVLM_OK;
     if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
@@ -240,7 +244,7 @@ pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *
     p.n_kv_heads = heads->n_kv_heads;
     p.scale = scale_of(heads);
     hipError_t e = heads->dtype == PEVLM_BF16 ? launch_attn_bf16(p, heads->head_dim, false, hs)
-                                              : launch_attn_f32(p, heads->head_dim, false, hs);
+                                                : launch_attn_f32(p, heads->head_dim, false, hs);
     if (e != hipSuccess) return hip_fail(e, "block-prefill launch");
     return PEVLM_OK;
 }

@@ -5,55 +5,21 @@
 // attention (Eq. 5).
 //
 // Tiling.  A workgroup of 4 wavefronts owns one work item (<= 128 query rows of one head); wave w
-// owns rows 32w..32w+31.  Keys are staged 64 at a time in LDS (K and V tiles, XOR-swizzled 16-byte
-// chunks).  Scores are formed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in the
-// accumulator layout a lane then holds 16 keys of ONE query (column = lane % 32), so the softmax
-// row reduction is 15 in-lane max/add operations and a single exchange with lane ^ 32.  The same
+// owns rows 32w..32w+31; two workgroups share a compute unit (two wavefronts per SIMD).  Keys are
+// staged 64 at a time in LDS (K and V tiles, XOR-swizzled 16-byte chunks, direct global->LDS loads,
+// two stages each).  Scores are formed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in
+// the accumulator layout a lane then holds 16 keys of ONE query (column = lane % 32), so the softmax
+// row reduction is in-lane max3/add chains and a single exchange with lane ^ 32.  The same
 // registers, converted to bf16, are directly the B operand of O^T += V^T P^T; V^T fragments come
 // from LDS through the transposing read ds_read_b64_tr_b16.
-#include "common.h"
+//
+// Schedule inside a wavefront (software pipeline over key tiles): the value MFMAs of tile t-1 are
+// issued interleaved with the vector-ALU work that turns the scores of tile t into weights, so the
+// matrix cores and the vector ALU of a SIMD overlap within one instruction stream as well as
+// across the two resident wavefronts.
+#include "bf16_device.h"
 
 namespace pevlm {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
-
-// 16-byte-per-lane load from global memory straight into LDS (no register staging).  The LDS
-// destination of lane i is lds_addr + 16 i; lds_addr must be wavefront-uniform.  Issued through
-// inline assembly so that the tile being consumed can be read while the next one is in flight: the
-// wait for completion is the explicit vmcnt(0) at the top of the tile loop.
-__device__ __forceinline__ void load_lds_16(const void *gptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n" ::"s"(lds_addr), "v"(gptr) : "memory");
-}
-
-__device__ __forceinline__ float max3f(float a, float b, float c)
-{
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
-// Same, with a wavefront-uniform 64-bit base address and a per-lane 32-bit byte offset.
-__device__ __forceinline__ void load_lds_16_base(const void *sbase, uint32_t voff, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
-}
-
-// Marks a pointer that is the same in every lane as wavefront-uniform (scalar registers).
-template <typename T>
-__device__ __forceinline__ const T *uniform_ptr(const T *p)
-{
-    const uint64_t v = (uint64_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return (const T *)(((uint64_t)hi << 32) | lo);
-}
 
 template <int D>
 struct TileCfg {
@@ -68,125 +34,96 @@ struct TileCfg {
     static constexpr int RPI = 1024 / ROWB;    // rows one wavefront-wide 16-byte-per-lane load covers
 };
 
-// One 64-key tile for one wavefront: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// masked = false: all 64 keys are visible to all 32 rows of the wave (the common case).
-// masked = true : the tile touches the diagonal or the end of the key range; nkc (1 or 2) 32-key
-//                 chunks are needed, entries are masked by key < kend and (causal) key <= row.
-// Kept as ONE inlined instance with wavefront-uniform flags: two specialised copies would meet at
-// a join that has to reconcile the 64 accumulator registers of O^T.
+// per-lane LDS offsets (the XOR swizzles depend on the lane only)
+struct LaneOff {
+    int32_t k_row_off, k_swz, v_row_off, v_ch_lo, v_swz, g32;
+};
+
+constexpr float kRescaleStep = 8.f;  // log2 units the row maximum may outgrow the reference maximum
+
+// S^T = K Q^T for the 64 keys of a staged tile: two independent accumulation chains (one per
+// 32-key chunk) issued alternately; A fragments (16 bytes per lane) are fetched half a tile ahead.
 template <int D>
-__device__ __forceinline__ void process_tile(const uint8_t *tk, const uint8_t *tv, const bf16x8 (&qf)[D / 16],
-                                             f32x16 (&o)[D / 32], float &m_run, float &l_run, float c_log2,
-                                             bool masked, int32_t nkc, int32_t k0, int32_t kend, bool causal,
-                                             int32_t my_row, int32_t lane)
+__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2])
 {
     using C = TileCfg<D>;
-    const int32_t l32 = lane & 31, g32 = lane >> 5;
-    // per-lane LDS offsets (the XOR swizzles depend on the lane only)
-    const int32_t k_row_off = l32 * C::ROWB;
-    const int32_t k_swz = l32 & (C::CH - 1);
-    const int32_t v_row_off = (g32 * 4 + ((lane & 15) >> 2)) * C::ROWB + (lane & 1) * 8;
-    const int32_t v_ch_lo = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
-    const int32_t v_swz = (lane >> 2) & C::VSW;
+    constexpr int HK = C::KSTEPS / 2;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
+#define PEVLM_KFRAG(kc, kk) \
+    (*reinterpret_cast<const bf16x8 *>(tk + (kc) * 32 * C::ROWB + L.k_row_off + ((((kk) * 2 + L.g32) ^ L.k_swz) << 4)))
+#pragma unroll
+    for (int kk = 0; kk < HK; ++kk) {
+        a0[kk] = PEVLM_KFRAG(0, kk);
+        a1[kk] = PEVLM_KFRAG(1, kk);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < HK; ++kk) {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], kk == 0 ? zero : s[0], 0, 0, 0);
+        a0[kk + HK] = PEVLM_KFRAG(0, kk + HK);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], kk == 0 ? zero : s[1], 0, 0, 0);
+        a1[kk + HK] = PEVLM_KFRAG(1, kk + HK);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = HK; kk < C::KSTEPS; ++kk) {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
+    }
+#undef PEVLM_KFRAG
+}
 
-    f32x16 s[2];
+// V^T fragments of 16 keys (k-step ks of the staged tile) for every 32-wide block of head_dim
+template <int D>
+__device__ __forceinline__ void read_v(const uint8_t *tv, const LaneOff &L, int ks, bf16x8 (&dst)[D / 32])
+{
+    using C = TileCfg<D>;
+#pragma unroll
+    for (int b = 0; b < C::DBLK; ++b)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const uint8_t *ptr = tv + (ks * 16 + tt * 8) * C::ROWB + L.v_row_off + (((b ^ L.v_swz) * 4 + L.v_ch_lo) << 4);
+            const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));
+            const bf16x4 rb = __builtin_bit_cast(bf16x4, r);
+            dst[b][tt * 4 + 0] = rb[0]; dst[b][tt * 4 + 1] = rb[1];
+            dst[b][tt * 4 + 2] = rb[2]; dst[b][tt * 4 + 3] = rb[3];
+        }
+}
+
+// entries a row must not see: beyond the key range, or (causal range) keys after the row
+__device__ __forceinline__ void mask_tile(f32x16 (&s)[2], int32_t k0, int32_t kend, bool causal, int32_t my_row, int32_t g32)
+{
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[kc][i] = 0.f;
-
-    // ---- S^T = K Q^T: A fragments (16 bytes per lane) are fetched one chunk ahead of the MFMAs ----
-    // The two 32-key chunks form two independent accumulation chains that are issued alternately.
-    bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
-    constexpr int HK = C::KSTEPS / 2;
-#pragma unroll
-    for (int kk = 0; kk < HK; ++kk) {
-        a0[kk] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + (((kk * 2 + g32) ^ k_swz) << 4));
-        a1[kk] = *reinterpret_cast<const bf16x8 *>(tk + 32 * C::ROWB + k_row_off + (((kk * 2 + g32) ^ k_swz) << 4));
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (nkc > 1) {
-#pragma unroll
-        for (int kk = 0; kk < HK; ++kk) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-            a0[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
-            a1[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + 32 * C::ROWB + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int i = 0; i < 16; ++i) {
+            const int32_t key = k0 + kc * 32 + (i >> 2) * 8 + g32 * 4 + (i & 3);
+            const bool ok = key < kend && (!causal || key <= my_row);
+            s[kc][i] = ok ? s[kc][i] : -INFINITY;
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kk = HK; kk < C::KSTEPS; ++kk) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
-        }
-    } else {
-#pragma unroll
-        for (int kk = 0; kk < HK; ++kk) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-            a0[kk + HK] = *reinterpret_cast<const bf16x8 *>(tk + k_row_off + ((((kk + HK) * 2 + g32) ^ k_swz) << 4));
-        }
-#pragma unroll
-        for (int kk = HK; kk < C::KSTEPS; ++kk) s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-    }
+}
 
-    // ---- V^T fragments of the first 16 keys: in flight during the softmax ----
-    bf16x8 va[C::DBLK];
-#define PEVLM_READ_V(dst, ks)                                                                                   \
-    _Pragma("unroll") for (int b = 0; b < C::DBLK; ++b) {                                                       \
-        _Pragma("unroll") for (int tt = 0; tt < 2; ++tt) {                                                      \
-            const uint8_t *ptr = tv + ((ks) * 16 + tt * 8) * C::ROWB + v_row_off + (((b ^ v_swz) * 4 + v_ch_lo) << 4); \
-            const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));                       \
-            const bf16x4 rb = __builtin_bit_cast(bf16x4, r);                                                    \
-            dst[b][tt * 4 + 0] = rb[0]; dst[b][tt * 4 + 1] = rb[1];                                             \
-            dst[b][tt * 4 + 2] = rb[2]; dst[b][tt * 4 + 3] = rb[3];                                             \
-        }                                                                                                       \
-    }
-    PEVLM_READ_V(va, 0);
-
-    // ---- mask ----
-    if (masked) {
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int32_t key = k0 + kc * 32 + (i >> 2) * 8 + g32 * 4 + (i & 3);
-                const bool ok = kc < nkc && key < kend && (!causal || key <= my_row);
-                s[kc][i] = ok ? s[kc][i] : -INFINITY;
-            }
-    }
-    // ---- online softmax: a lane holds 32 keys of its own query; its partner lane ^ 32 the others.
-    // The reference maximum m_run is only moved when some row's maximum grew by more than
-    // kRescaleStep (log2 units): weights are then at most 2^kRescaleStep, which fp32 sums and bf16
-    // weights carry without loss, and the 64 accumulator multiplies are skipped on almost every
-    // tile.  The result is unchanged in exact arithmetic: sum and values share one reference.
+// maximum over the 64 keys of the tile for this lane's row (both lanes of a row end up with it)
+__device__ __forceinline__ float row_max(const f32x16 (&s)[2])
+{
     float mx = max3f(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
     for (int i = 3; i < 31; i += 2) mx = max3f(mx, s[i >> 4][i & 15], s[(i + 1) >> 4][(i + 1) & 15]);
-    {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        const auto sl = __builtin_amdgcn_permlane32_swap(__float_as_uint(s[1][15]), __float_as_uint(s[1][15]), false, false);
-        mx = max3f(__uint_as_float(sw[0]), __uint_as_float(sw[1]), __uint_as_float(sl[0]));
-        mx = max3f(mx, __uint_as_float(sl[1]), mx);
-    }
-    constexpr float kRescaleStep = 8.f;
-    if (__any((mx - m_run) * c_log2 > kRescaleStep || m_run == -INFINITY)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);  // m_run = -inf gives 0
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int b = 0; b < C::DBLK; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
-    }
-    const float mc = (m_run == -INFINITY) ? 0.f : m_run * c_log2;
+    mx = fmaxf(mx, s[1][15]);
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+// weights p = exp2(c s - c m) of the tile (bf16 B fragments of the value MFMAs) and their sum over
+// this lane's 32 keys
+__device__ __forceinline__ void weights(const f32x16 (&s)[2], float mc, float c_log2, float &l_run, bf16x8 (&pf)[4])
+{
     float psum = 0.f;
-    bf16x8 pf[4];
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
@@ -196,24 +133,79 @@ __device__ __forceinline__ void process_tile(const uint8_t *tk, const uint8_t *t
             pf[kc * 2 + (i >> 3)][i & 7] = (__bf16)e;
         }
     l_run += psum;
+}
 
-    // ---- O^T += V^T P^T, V^T fragments one k-step ahead ----
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 vb[C::DBLK];
-    const int32_t nks = nkc * 2;
+// O^T += V^T P^T for a staged V tile (16 MFMAs per 32 values of head_dim ... 4 k-steps x DBLK blocks)
+template <int D>
+__device__ __forceinline__ void pv_tile(const uint8_t *tv, const LaneOff &L, const bf16x8 (&pf)[4], f32x16 (&o)[D / 32])
+{
+    using C = TileCfg<D>;
+    bf16x8 va[C::DBLK], vb[C::DBLK];
+    read_v<D>(tv, L, 0, va);
 #pragma unroll
     for (int ks = 0; ks < 4; ks += 2) {
-        if (ks >= nks) break;
-        PEVLM_READ_V(vb, ks + 1);
+        read_v<D>(tv, L, ks + 1, vb);
 #pragma unroll
         for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[b], pf[ks], o[b], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks + 2 < 4 && ks + 2 < nks) PEVLM_READ_V(va, ks + 2);
+        if (ks + 2 < 4) read_v<D>(tv, L, ks + 2, va);
 #pragma unroll
         for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[b], pf[ks + 1], o[b], 0, 0, 0);
+    }
+}
+
+// One V^T fragment: 16 keys (k-step ks) x the b-th 32-wide block of head_dim
+template <int D>
+__device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L, int ks, int b)
+{
+    using C = TileCfg<D>;
+    bf16x8 dst;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        const uint8_t *ptr = tv + (ks * 16 + tt * 8) * C::ROWB + L.v_row_off + (((b ^ L.v_swz) * 4 + L.v_ch_lo) << 4);
+        const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));
+        const bf16x4 rb = __builtin_bit_cast(bf16x4, r);
+        dst[tt * 4 + 0] = rb[0]; dst[tt * 4 + 1] = rb[1];
+        dst[tt * 4 + 2] = rb[2]; dst[tt * 4 + 3] = rb[3];
+    }
+    return dst;
+}
+
+// The pipelined step: O^T += V^T P^T of the previous tile (matrix cores) issued one MFMA at a time,
+// each followed by the vector-ALU work for a few weights of the current tile,
+// p = exp2(c s - c m) -> bf16, so that both pipes of the SIMD run from one instruction stream.
+// V^T fragments are read one k-step ahead of their MFMA.
+template <int D>
+__device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const bf16x8 (&pf_prev)[4],
+                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float mc, float c_log2,
+                                                    float &l_run, bf16x8 (&pf_new)[4])
+{
+    using C = TileCfg<D>;
+    constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
+    constexpr int EPS = 32 / NM;     // weights formed per MFMA
+    bf16x8 vf[2][C::DBLK];
+#pragma unroll
+    for (int b = 0; b < C::DBLK; ++b) vf[0][b] = read_v_one<D>(tv_prev, L, 0, b);
+    float psum = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int n = 0; n < NM; ++n) {
+        const int ks = n / C::DBLK, b = n % C::DBLK;
+        if (ks + 1 < 4) vf[(ks + 1) & 1][b] = read_v_one<D>(tv_prev, L, ks + 1, b);
+        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1][b], pf_prev[ks], o[b], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < EPS; ++e) {
+            const int idx = n * EPS + e, kc = idx >> 4, i = idx & 15;
+            const float ex = __builtin_amdgcn_exp2f(s[kc][i] * c_log2 - mc);
+            psum += ex;
+            pf_new[kc * 2 + (i >> 3)][i & 7] = (__bf16)ex;
+        }
+        // keep the sum and each completed fragment here (plain arithmetic would otherwise be
+        // emitted after the last MFMA)
+        asm volatile("" : "+v"(psum));
+        if (((n + 1) * EPS) % 8 == 0) asm volatile("" : "+v"(pf_new[((n + 1) * EPS) / 8 - 1]));
         __builtin_amdgcn_sched_barrier(0);
     }
-#undef PEVLM_READ_V
+    l_run += psum;
 }
 
 template <int D, bool PARTIAL>
@@ -245,13 +237,22 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     const int32_t l32 = lane & 31, g32 = lane >> 5;
     const uint16_t *Q = (const uint16_t *)p.q, *K = (const uint16_t *)p.k, *V = (const uint16_t *)p.v;
 
-    // ---- this lane's query row, Q fragments (B operand of S^T = K Q^T) stay in registers ----
+    LaneOff L;
+    L.g32 = g32;
+    L.k_row_off = l32 * ROWB;
+    L.k_swz = l32 & (CH - 1);
+    L.v_row_off = (g32 * 4 + ((lane & 15) >> 2)) * ROWB + (lane & 1) * 8;
+    L.v_ch_lo = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+    L.v_swz = (lane >> 2) & VSW;
+
+    // ---- this lane's query row ----
     const int32_t row_in_tile = wave * 32 + l32;
     const bool row_valid = row_in_tile < it.q_rows;
     const int32_t my_row = it.q_start + (row_valid ? row_in_tile : it.q_rows - 1);
     const bool wave_active = wave * 32 < it.q_rows;
     const int32_t wr_lo = it.q_start + wave * 32;
     const int32_t wr_hi = it.q_start + ((wave * 32 + 31 < it.q_rows) ? wave * 32 + 31 : it.q_rows - 1);
+
     const uint32_t lds_k_addr = (uint32_t)(size_t)LDS_PTR(void, lds_k);
     const uint32_t lds_v_addr = (uint32_t)(size_t)LDS_PTR(void, lds_v);
     // Q rows of the wave are fetched with whole-row (coalesced) direct-to-LDS loads into a
@@ -260,7 +261,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     constexpr int WSLICE = 32 * ROWB;  // bytes of 32 rows
     uint8_t *const wave_slice = (wave < 2 ? lds_k : lds_v) + TILEB + (wave & 1) * WSLICE;
     const uint32_t wave_slice_addr = (wave < 2 ? lds_k_addr : lds_v_addr) + TILEB + (wave & 1) * WSLICE;
-    bf16x8 qf[KSTEPS];
 #pragma unroll
     for (int j = 0; j < WSLICE / 1024; ++j) {
         const int32_t rl = j * RPI + lane / CH, cpos = lane % CH;
@@ -270,22 +270,22 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
                     wave_slice_addr + j * 1024);
     }
 
-    const float c_log2 = p.scale * 1.4426950408889634f;
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x16 o[DBLK];
-#pragma unroll
-    for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
-
     const int32_t n_full_tiles = (it.full_len + KT - 1) / KT;
-    const int32_t n_tiles = n_full_tiles + (it.diag_len + KT - 1) / KT;
+    const int32_t n_diag_tiles = (it.diag_len + KT - 1) / KT;
+    const int32_t n_tiles = n_full_tiles + n_diag_tiles;
+    // tiles this wave computes: all fully visible ones, and the causal ones that start at or before
+    // its last row (the rest is masked for every row of the wave)
+    int32_t n_w = 0;
+    if (wave_active) {
+        int32_t nd = wr_hi >= it.diag_start ? (wr_hi - it.diag_start) / KT + 1 : 0;
+        n_w = n_full_tiles + (nd < n_diag_tiles ? nd : n_diag_tiles);
+    }
 
     // ---- K/V tiles go straight from global memory into LDS (16 bytes per lane): a wavefront
     // instruction fills 1 KB of contiguous LDS, i.e. RPI whole rows; the XOR swizzle is applied by
-    // choosing which 16-byte chunk of the row each lane fetches.  Two LDS stages: tile t+1 streams
-    // in while tile t is consumed.  Rows past the key range repeat its last key (their scores are
-    // masked, their values stay finite).
+    // choosing which 16-byte chunk of the row each lane fetches.  Two LDS stages per tensor: K(t+1)
+    // and V(t) stream in while tile t's scores and tile t-1's values are computed.  Rows past the
+    // key range repeat its last key (their scores are masked, their values stay finite).
 #define PEVLM_TILE_RANGE(t, k0, kend, causal)                 \
     do {                                                      \
         if ((t) < n_full_tiles) {                             \
@@ -307,62 +307,130 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         koff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ (row & (CH - 1))) << 3)) * 2);
         voff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ ((row & VSW) << 2)) << 3)) * 2);
     }
-#define PEVLM_ISSUE_TILE(t, stage)                                                                   \
-    do {                                                                                             \
-        int32_t pk0, pkend;                                                                          \
-        bool pcausal;                                                                                \
-        PEVLM_TILE_RANGE(t, pk0, pkend, pcausal);                                                    \
-        (void)pcausal;                                                                               \
-        if (pk0 + KT <= pkend) {                                                                     \
-            const uint16_t *kb = uniform_ptr(K + ((int64_t)pk0 * Hkv + g) * D);                      \
-            const uint16_t *vb = uniform_ptr(V + ((int64_t)pk0 * Hkv + g) * D);                      \
-            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                        \
-                const uint32_t dst = (uint32_t)((stage) * TILEB + (j * 4 + wave) * RPI * ROWB);      \
-                load_lds_16_base(kb, koff[j], lds_k_addr + dst);                                     \
-                load_lds_16_base(vb, voff[j], lds_v_addr + dst);                                     \
-            }                                                                                        \
-        } else {                                                                                     \
-            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                        \
-                const int32_t rbase = (j * 4 + wave) * RPI;                                          \
-                const int32_t row = rbase + lane / CH, cpos = lane % CH;                             \
-                int32_t key = pk0 + row;                                                             \
-                key = key < pkend ? key : pkend - 1;                                                 \
-                const int64_t roff = ((int64_t)key * Hkv + g) * D;                                   \
-                const uint32_t dst = (uint32_t)((stage) * TILEB + rbase * ROWB);                     \
-                load_lds_16(K + roff + ((cpos ^ (row & (CH - 1))) << 3), lds_k_addr + dst);          \
-                load_lds_16(V + roff + ((cpos ^ ((row & VSW) << 2)) << 3), lds_v_addr + dst);        \
-            }                                                                                        \
-        }                                                                                            \
+#define PEVLM_ISSUE(T, toff, swz_expr, lds_base_addr, t, stage)                                       \
+    do {                                                                                              \
+        int32_t pk0, pkend;                                                                           \
+        bool pcausal;                                                                                 \
+        PEVLM_TILE_RANGE(t, pk0, pkend, pcausal);                                                     \
+        (void)pcausal;                                                                                \
+        if (pk0 + KT <= pkend) {                                                                      \
+            const uint16_t *tb = uniform_ptr(T + ((int64_t)pk0 * Hkv + g) * D);                       \
+            _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                           \
+                load_lds_16_base(tb, toff[j], lds_base_addr + (stage) * TILEB + (j * 4 + wave) * RPI * ROWB); \
+        } else {                                                                                      \
+            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                         \
+                const int32_t rbase = (j * 4 + wave) * RPI;                                           \
+                const int32_t row = rbase + lane / CH, cpos = lane % CH;                              \
+                int32_t key = pk0 + row;                                                              \
+                key = key < pkend ? key : pkend - 1;                                                  \
+                load_lds_16(T + ((int64_t)key * Hkv + g) * D + ((cpos ^ (swz_expr)) << 3),            \
+                            lds_base_addr + (stage) * TILEB + rbase * ROWB);                          \
+            }                                                                                         \
+        }                                                                                             \
+    } while (0)
+#define PEVLM_ISSUE_K(t) PEVLM_ISSUE(K, koff, (row & (CH - 1)), lds_k_addr, t, (t) & 1)
+#define PEVLM_ISSUE_V(t) PEVLM_ISSUE(V, voff, ((row & VSW) << 2), lds_v_addr, t, (t) & 1)
+    // top of tile t: K(t) and V(t-1) have landed for everybody, everybody is done with K(t-1) and
+    // V(t-2); then K(t+1) and V(t) are put in flight
+#define PEVLM_TOP(t)                                                   \
+    do {                                                               \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */             \
+        __syncthreads();                                               \
+        if ((t) + 1 < n_tiles) PEVLM_ISSUE_K((t) + 1);                 \
+        PEVLM_ISSUE_V(t);                                              \
     } while (0)
 
     if (n_tiles > 0) {
-        PEVLM_ISSUE_TILE(0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD));  // all but the tile-0 loads: Q has landed
+        PEVLM_ISSUE_K(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | NLD);  // all but the K(0) loads: Q has landed
     } else {
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     asm volatile("" ::: "memory");
+    bf16x8 qf[KSTEPS];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk)
         qf[kk] = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
-    for (int32_t t = 0; t < n_tiles; ++t) {
-        const int32_t stage = t & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of tile t has landed in LDS
-        __syncthreads();                     // ... and everyone's; all waves are done with tile t-1
-        if (t + 1 < n_tiles) PEVLM_ISSUE_TILE(t + 1, stage ^ 1);
-        const uint8_t *tk = lds_k + stage * TILEB;
-        const uint8_t *tv = lds_v + stage * TILEB;
-        int32_t k0, kend;
-        bool causal;
-        PEVLM_TILE_RANGE(t, k0, kend, causal);
 
-        // keys of this tile the wave needs, in 32-key chunks
-        int32_t lim = kend - k0;
-        if (causal && wr_hi - k0 + 1 < lim) lim = wr_hi - k0 + 1;
-        const int32_t nkc = (!wave_active || lim <= 0) ? 0 : (lim > 32 ? 2 : 1);
-        if (nkc == 0) continue;
-        const bool need_mask = (k0 + nkc * 32 > kend) || (causal && (k0 + nkc * 32 - 1 > wr_lo));
-        process_tile<D>(tk, tv, qf, o, m_run, l_run, c_log2, need_mask || nkc < 2, nkc, k0, kend, causal, my_row, lane);
+    const float c_log2 = p.scale * 1.4426950408889634f;
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 o[DBLK];
+#pragma unroll
+    for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
+
+    // scores of tile t -> s (masked where the tile touches the diagonal or the end of its range),
+    // row maxima -> mx
+#define PEVLM_SCORES(t)                                                                   \
+    do {                                                                                  \
+        int32_t k0, kend;                                                                 \
+        bool causal;                                                                      \
+        PEVLM_TILE_RANGE(t, k0, kend, causal);                                            \
+        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, s);                                  \
+        if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo)))                        \
+            mask_tile(s, k0, kend, causal, my_row, g32);                                  \
+        mx = row_max(s);                                                                  \
+    } while (0)
+    // The reference maximum m_run moves only when some row's maximum outgrew it by more than
+    // kRescaleStep: weights then stay below 2^kRescaleStep, which fp32 sums and bf16 weights carry
+    // without loss, and the accumulator multiplies are skipped on almost every tile.  The weights
+    // of the previous tile that still wait for their value MFMAs are scaled along.
+#define PEVLM_RESCALE(HAS_PREV)                                                                       \
+    do {                                                                                              \
+        if (__any((mx - m_run) * c_log2 > kRescaleStep || m_run == -INFINITY)) {                      \
+            const float m_new = fmaxf(m_run, mx);                                                     \
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                   \
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2); /* -inf -> 0 */     \
+            m_run = m_new;                                                                            \
+            l_run *= alpha;                                                                           \
+            _Pragma("unroll") for (int b = 0; b < DBLK; ++b)                                          \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) o[b][i] *= alpha;                      \
+            if (HAS_PREV) {                                                                           \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                         \
+                    _Pragma("unroll") for (int i = 0; i < 8; ++i)                                     \
+                        pf_prev[j][i] = (__bf16)((float)pf_prev[j][i] * alpha);                       \
+            }                                                                                         \
+        }                                                                                             \
+    } while (0)
+
+    f32x16 s[2];
+    float mx;
+    bf16x8 pf_prev[4];
+    if (n_w > 0) {
+        PEVLM_TOP(0);
+        PEVLM_SCORES(0);
+        PEVLM_RESCALE(false);
+        weights(s, (m_run == -INFINITY) ? 0.f : m_run * c_log2, c_log2, l_run, pf_prev);
+        for (int32_t t = 1; t < n_w; ++t) {
+            PEVLM_TOP(t);
+            PEVLM_SCORES(t);
+            PEVLM_RESCALE(true);
+            // values of tile t-1 (matrix cores) under the weights of tile t (vector ALU)
+            bf16x8 pf_new[4];
+            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s,
+                                   (m_run == -INFINITY) ? 0.f : m_run * c_log2, c_log2, l_run, pf_new);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
+        }
+    }
+    // Every wavefront passes the top of all n_tiles tiles and one final barrier.  The values of the
+    // last tile a wave computed are added once their V tile is known to be in LDS.
+    int32_t t_rest = n_w;
+    bool synced = false;
+    if (n_w > 0 && n_w < n_tiles) {
+        PEVLM_TOP(n_w);
+        t_rest = n_w + 1;
+    } else if (n_w == n_tiles) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        synced = true;
+    }
+    if (n_w > 0) pv_tile<D>(lds_v + ((n_w - 1) & 1) * TILEB, L, pf_prev, o);
+    for (int32_t t = t_rest; t < n_tiles; ++t) PEVLM_TOP(t);
+    if (!synced) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
     }
 
     // ---- epilogue ----
@@ -384,11 +452,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             p.part_ml[(slot * Hq + h) * 2 + 1] = l_tot;
         }
     } else {
-        // O^T fragments -> wave-private LDS slice of the stage the last tile did not use (row-major
-        // bf16, swizzled), then whole-row 16-byte stores.
+        // O^T fragments -> wave-private LDS slice (row-major bf16, swizzled), then whole-row 16-byte
+        // stores.  The slice lies in the stage the last tile does not use: a wavefront may still be
+        // adding the values of the last tile out of the other stage.
         const float inv = 1.f / l_tot;
-        const int32_t free_stage = n_tiles & 1;
-        uint8_t *const oslice = (wave < 2 ? lds_k : lds_v) + free_stage * TILEB + (wave & 1) * WSLICE;
+        uint8_t *const oslice = (wave < 2 ? lds_k : lds_v) + (n_tiles & 1) * TILEB + (wave & 1) * WSLICE;
 #pragma unroll
         for (int b = 0; b < DBLK; ++b)
 #pragma unroll

@@ -118,14 +118,14 @@ def test_bf16_gpu_worklist_equals_host_enumeration():
     out = torch.zeros_like(q)
     ws = P.pevlm_block_prefill_attn(q, k, v, out, lay, heads)
     torch.cuda.synchronize()
-    host = P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows())
+    host = P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads))
     n = len(host)
     dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
     host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
     assert np.array_equal(dev_items, host_items)
     ws = P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=5)
     torch.cuda.synchronize()
-    host = P.pevlm_query_worklist_host(lay, P.pevlm_prefill_tile_rows(), 5)
+    host = P.pevlm_query_worklist_host(lay, P.pevlm_query_tile_rows(heads), 5)
     n = len(host)
     dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
     host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)

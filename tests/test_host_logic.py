@@ -51,7 +51,7 @@ def expand_items(items, T):
 
 
 @pytest.mark.parametrize("seqs", LAYOUTS)
-@pytest.mark.parametrize("tile_rows", [1, 16, 128])
+@pytest.mark.parametrize("tile_rows", [1, 16, 128, 256])
 def test_prefill_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows):
     lay = P.Layout.from_seqs(seqs)
     T = lay.total_tokens
@@ -156,7 +156,7 @@ def test_argument_validation_without_gpu():
 def test_workspace_sizes_cover_items_and_partials():
     lay = P.Layout.from_seqs([(256, 1024, 65536, 128)])
     heads = P.Heads(28, 4, 128, "bf16")
-    n = len(P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows()))
+    n = len(P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads)))
     assert P.pevlm_block_prefill_workspace_bytes(lay, heads) >= n * ctypes.sizeof(P.WorkItem)
     for ns in (1, 8, 64):
         need = ns * 128 * 28 * (128 + 2) * 4 + 128 * 4 + ns * ctypes.sizeof(P.WorkItem)
