@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+# HBM bytes per block-prefill launch from the FETCH_SIZE / WRITE_SIZE passes recorded in
+# profiles/attn_bf16_prefill_c3_counters.md (scaled by the same counters on a 1 GiB device copy)
+MEASURED_PREFILL_TRAFFIC_BYTES = {"c3": 1.081e9}
 HBM_PEAK_GBS = 8000.0
 
 
@@ -135,7 +138,7 @@ def main():
             "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(f_prefill / (ms_prefill * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(args.workload),
         },
         "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
     }
