@@ -43,12 +43,15 @@ constexpr float kRescaleStep = 8.f;  // log2 units the row maximum may outgrow t
 
 // S^T = K Q^T for the 64 keys of a staged tile: two independent accumulation chains (one per
 // 32-key chunk) issued alternately; A fragments (16 bytes per lane) are fetched half a tile ahead.
+// Q is pre-multiplied by scale*log2(e) and the chains start from `init` = minus the row's reference
+// maximum, so the accumulators come out as the exponents of the softmax weights: no per-score
+// multiply or subtract is left for the vector ALU.
 template <int D>
-__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2])
+__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], const f32x16 &init,
+                                        f32x16 (&s)[2])
 {
     using C = TileCfg<D>;
     constexpr int HK = C::KSTEPS / 2;
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
 #define PEVLM_KFRAG(kc, kk) \
     (*reinterpret_cast<const bf16x8 *>(tk + (kc) * 32 * C::ROWB + L.k_row_off + ((((kk) * 2 + L.g32) ^ L.k_swz) << 4)))
@@ -60,9 +63,9 @@ __device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, con
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < HK; ++kk) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], kk == 0 ? zero : s[0], 0, 0, 0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], kk == 0 ? init : s[0], 0, 0, 0);
         a0[kk + HK] = PEVLM_KFRAG(0, kk + HK);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], kk == 0 ? zero : s[1], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], kk == 0 ? init : s[1], 0, 0, 0);
         a1[kk + HK] = PEVLM_KFRAG(1, kk + HK);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -119,25 +122,43 @@ __device__ __forceinline__ float row_max(const f32x16 (&s)[2])
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-// weights p = exp2(c s - c m) of the tile (bf16 B fragments of the value MFMAs) and their sum over
-// this lane's 32 keys
-__device__ __forceinline__ void weights(const f32x16 (&s)[2], float mc, float c_log2, float &l_run, bf16x8 (&pf)[4])
+// weights p = exp2(s') of the tile, s' being the exponent left by qk_tile: bf16 pairs (B fragments
+// of the value MFMAs), their sum over this lane's 32 keys (dot product of each pair with (1, 1)), and
+// the OR of all pair bit patterns, from which "some weight reached 2^kRescaleStep" is read off.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float &psum, uint32_t &orb)
 {
-    float psum = 0.f;
+    bf16x2 pr;
+    pr[0] = (__bf16)__builtin_amdgcn_exp2f(s0);
+    pr[1] = (__bf16)__builtin_amdgcn_exp2f(s1);
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+    const uint32_t word = __builtin_bit_cast(uint32_t, pr);
+    orb |= word;
+    return word;
+}
+
+__device__ __forceinline__ void weights(const f32x16 (&s)[2], float &psum, uint32_t &orb, u32x4 (&pf)[4])
+{
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(s[kc][i] * c_log2 - mc);
-            psum += e;
-            pf[kc * 2 + (i >> 3)][i & 7] = (__bf16)e;
-        }
-    l_run += psum;
+        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], psum, orb);
+}
+
+// true when a bf16 pair pattern (or an OR of such patterns of non-negative values) holds a value
+// >= 2^kRescaleStep (also inf / nan)
+__device__ __forceinline__ bool pair_reached_step(uint32_t orb)
+{
+    constexpr uint32_t kBits = 0x3F80u + ((uint32_t)kRescaleStep << 7);  // bf16 pattern of 2^kRescaleStep
+    return (orb >> 16) >= kBits || (orb & 0xFFFFu) >= kBits;
 }
 
 // O^T += V^T P^T for a staged V tile (16 MFMAs per 32 values of head_dim ... 4 k-steps x DBLK blocks)
 template <int D>
-__device__ __forceinline__ void pv_tile(const uint8_t *tv, const LaneOff &L, const bf16x8 (&pf)[4], f32x16 (&o)[D / 32])
+__device__ __forceinline__ void pv_tile(const uint8_t *tv, const LaneOff &L, const u32x4 (&pf)[4], f32x16 (&o)[D / 32])
 {
     using C = TileCfg<D>;
     bf16x8 va[C::DBLK], vb[C::DBLK];
@@ -146,10 +167,10 @@ __device__ __forceinline__ void pv_tile(const uint8_t *tv, const LaneOff &L, con
     for (int ks = 0; ks < 4; ks += 2) {
         read_v<D>(tv, L, ks + 1, vb);
 #pragma unroll
-        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[b], pf[ks], o[b], 0, 0, 0);
+        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[b], __builtin_bit_cast(bf16x8, pf[ks]), o[b], 0, 0, 0);
         if (ks + 2 < 4) read_v<D>(tv, L, ks + 2, va);
 #pragma unroll
-        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[b], pf[ks + 1], o[b], 0, 0, 0);
+        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[b], __builtin_bit_cast(bf16x8, pf[ks + 1]), o[b], 0, 0, 0);
     }
 }
 
@@ -171,41 +192,35 @@ __device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L
 }
 
 // The pipelined step: O^T += V^T P^T of the previous tile (matrix cores) issued one MFMA at a time,
-// each followed by the vector-ALU work for a few weights of the current tile,
-// p = exp2(c s - c m) -> bf16, so that both pipes of the SIMD run from one instruction stream.
-// V^T fragments are read one k-step ahead of their MFMA.
+// each followed by the vector-ALU work for a pair (or two) of weights of the current tile, so that
+// both pipes of the SIMD run from one instruction stream.  V^T fragments are read one k-step ahead.
 template <int D>
-__device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const bf16x8 (&pf_prev)[4],
-                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float mc, float c_log2,
-                                                    float &l_run, bf16x8 (&pf_new)[4])
+__device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
+                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float &psum,
+                                                    uint32_t &orb, u32x4 (&pf_new)[4])
 {
     using C = TileCfg<D>;
     constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
-    constexpr int EPS = 32 / NM;     // weights formed per MFMA
+    constexpr int PPM = 16 / NM;     // weight pairs formed per MFMA
     bf16x8 vf[2][C::DBLK];
 #pragma unroll
     for (int b = 0; b < C::DBLK; ++b) vf[0][b] = read_v_one<D>(tv_prev, L, 0, b);
-    float psum = 0.f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int n = 0; n < NM; ++n) {
         const int ks = n / C::DBLK, b = n % C::DBLK;
         if (ks + 1 < 4) vf[(ks + 1) & 1][b] = read_v_one<D>(tv_prev, L, ks + 1, b);
-        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1][b], pf_prev[ks], o[b], 0, 0, 0);
+        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1][b], __builtin_bit_cast(bf16x8, pf_prev[ks]), o[b], 0, 0, 0);
 #pragma unroll
-        for (int e = 0; e < EPS; ++e) {
-            const int idx = n * EPS + e, kc = idx >> 4, i = idx & 15;
-            const float ex = __builtin_amdgcn_exp2f(s[kc][i] * c_log2 - mc);
-            psum += ex;
-            pf_new[kc * 2 + (i >> 3)][i & 7] = (__bf16)ex;
+        for (int e = 0; e < PPM; ++e) {
+            const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;
+            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], psum, orb);
         }
-        // keep the sum and each completed fragment here (plain arithmetic would otherwise be
-        // emitted after the last MFMA)
-        asm volatile("" : "+v"(psum));
-        if (((n + 1) * EPS) % 8 == 0) asm volatile("" : "+v"(pf_new[((n + 1) * EPS) / 8 - 1]));
+        // keep the running values here (plain arithmetic would otherwise be emitted after the last MFMA)
+        asm volatile("" : "+v"(psum), "+v"(orb));
+        if (((n + 1) * PPM) % 4 == 0) asm volatile("" : "+v"(pf_new[((n + 1) * PPM) / 4 - 1]));
         __builtin_amdgcn_sched_barrier(0);
     }
-    l_run += psum;
 }
 
 template <int D, bool PARTIAL>
@@ -347,69 +362,88 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     asm volatile("" ::: "memory");
+    // Q fragments, multiplied by scale*log2(e) (rounded to bf16 again) so that the score MFMAs
+    // deliver base-2 exponents directly
+    const float c_log2 = p.scale * 1.4426950408889634f;
     bf16x8 qf[KSTEPS];
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk)
-        qf[kk] = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        const bf16x8 raw = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) qf[kk][j] = (__bf16)((float)raw[j] * c_log2);
+    }
 
-    const float c_log2 = p.scale * 1.4426950408889634f;
-    float m_run = -INFINITY, l_run = 0.f;
+    // m_ref: reference maximum of this lane's row in base-2 exponent units (-inf: none yet);
+    // neg_ref: sixteen copies of -m_ref (0 while there is none), the start value of the score chains
+    float m_ref = -INFINITY, l_run = 0.f;
+    f32x16 neg_ref;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_ref[i] = 0.f;
     f32x16 o[DBLK];
 #pragma unroll
     for (int b = 0; b < DBLK; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
-    // scores of tile t -> s (masked where the tile touches the diagonal or the end of its range),
-    // row maxima -> mx
+    // exponents of tile t -> s (masked where the tile touches the diagonal or the end of its range)
 #define PEVLM_SCORES(t)                                                                   \
     do {                                                                                  \
         int32_t k0, kend;                                                                 \
         bool causal;                                                                      \
         PEVLM_TILE_RANGE(t, k0, kend, causal);                                            \
-        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, s);                                  \
+        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, neg_ref, s);                         \
         if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo)))                        \
             mask_tile(s, k0, kend, causal, my_row, g32);                                  \
-        mx = row_max(s);                                                                  \
     } while (0)
-    // The reference maximum m_run moves only when some row's maximum outgrew it by more than
-    // kRescaleStep: weights then stay below 2^kRescaleStep, which fp32 sums and bf16 weights carry
-    // without loss, and the accumulator multiplies are skipped on almost every tile.  The weights
-    // of the previous tile that still wait for their value MFMAs are scaled along.
-#define PEVLM_RESCALE(HAS_PREV)                                                                       \
+    // The weights of a tile are first formed against the reference maximum the row already has.
+    // Only if some weight reached 2^kRescaleStep (or a row has no reference yet) is the row maximum
+    // of the tile computed, the reference raised, o and l scaled down and the tile's weights formed
+    // again: weights stay below 2^kRescaleStep, which fp32 sums and bf16 weights carry without loss,
+    // and on almost every tile the vector ALU only does exp2, convert and sum.
+#define PEVLM_FIX_REFERENCE()                                                                         \
     do {                                                                                              \
-        if (__any((mx - m_run) * c_log2 > kRescaleStep || m_run == -INFINITY)) {                      \
-            const float m_new = fmaxf(m_run, mx);                                                     \
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                   \
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2); /* -inf -> 0 */     \
-            m_run = m_new;                                                                            \
+        if (__any(pair_reached_step(orb) || m_ref == -INFINITY)) {                                    \
+            const float mx = row_max(s);                                                              \
+            const bool has = m_ref != -INFINITY;                                                      \
+            const float shift = has ? fmaxf(mx, 0.f) : (mx == -INFINITY ? 0.f : mx);                  \
+            const float alpha = has ? __builtin_amdgcn_exp2f(-shift) : 1.f;                           \
+            m_ref = has ? m_ref + shift : mx;                                                         \
+            _Pragma("unroll") for (int kc = 0; kc < 2; ++kc)                                          \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) s[kc][i] -= shift;                     \
+            psum = 0.f;                                                                               \
+            orb = 0u;                                                                                 \
+            weights(s, psum, orb, pf_new);                                                            \
             l_run *= alpha;                                                                           \
             _Pragma("unroll") for (int b = 0; b < DBLK; ++b)                                          \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) o[b][i] *= alpha;                      \
-            if (HAS_PREV) {                                                                           \
-                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                         \
-                    _Pragma("unroll") for (int i = 0; i < 8; ++i)                                     \
-                        pf_prev[j][i] = (__bf16)((float)pf_prev[j][i] * alpha);                       \
-            }                                                                                         \
+            const float nr = (m_ref == -INFINITY) ? 0.f : -m_ref;                                     \
+            _Pragma("unroll") for (int i = 0; i < 16; ++i) neg_ref[i] = nr;                           \
         }                                                                                             \
     } while (0)
 
     f32x16 s[2];
-    float mx;
-    bf16x8 pf_prev[4];
+    u32x4 pf_prev[4], pf_new[4];
+    float psum;
+    uint32_t orb;
     if (n_w > 0) {
         PEVLM_TOP(0);
         PEVLM_SCORES(0);
-        PEVLM_RESCALE(false);
-        weights(s, (m_run == -INFINITY) ? 0.f : m_run * c_log2, c_log2, l_run, pf_prev);
+        psum = 0.f;
+        orb = 0u;
+        weights(s, psum, orb, pf_new);
+        PEVLM_FIX_REFERENCE();
+        l_run += psum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
         for (int32_t t = 1; t < n_w; ++t) {
             PEVLM_TOP(t);
             PEVLM_SCORES(t);
-            PEVLM_RESCALE(true);
             // values of tile t-1 (matrix cores) under the weights of tile t (vector ALU)
-            bf16x8 pf_new[4];
-            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s,
-                                   (m_run == -INFINITY) ? 0.f : m_run * c_log2, c_log2, l_run, pf_new);
+            psum = 0.f;
+            orb = 0u;
+            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, psum, orb, pf_new);
+            PEVLM_FIX_REFERENCE();
+            l_run += psum;
 #pragma unroll
             for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
         }
@@ -448,7 +482,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
                 *reinterpret_cast<f32x4 *>(acc + d) = v4;
             }
         if (g32 == 0) {
-            p.part_ml[(slot * Hq + h) * 2] = m_run;
+            p.part_ml[(slot * Hq + h) * 2] = m_ref / c_log2;  // back to raw score units (-inf stays)
             p.part_ml[(slot * Hq + h) * 2 + 1] = l_tot;
         }
     } else {
@@ -479,7 +513,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             if (wave * 32 + rl < it.q_rows)
                 *reinterpret_cast<uint4 *>(obase + ((int64_t)(it.q_start + wave * 32 + rl) * Hq + h) * D + cpos * 8) = val;
         }
-        if (p.lse && g32 == 0 && row_valid) p.lse[(int64_t)my_row * Hq + h] = m_run * p.scale + __logf(l_tot);
+        if (p.lse && g32 == 0 && row_valid) p.lse[(int64_t)my_row * Hq + h] = (m_ref + __log2f(l_tot)) * 0.69314718056f;
     }
 }
 
