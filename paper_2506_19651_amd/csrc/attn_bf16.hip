@@ -43,15 +43,12 @@ constexpr float kRescaleStep = 8.f;  // log2 units the row maximum may outgrow t
 
 // S^T = K Q^T for the 64 keys of a staged tile: two independent accumulation chains (one per
 // 32-key chunk) issued alternately; A fragments (16 bytes per lane) are fetched half a tile ahead.
-// Q is pre-multiplied by scale*log2(e) and the chains start from `init` = minus the row's reference
-// maximum, so the accumulators come out as the exponents of the softmax weights: no per-score
-// multiply or subtract is left for the vector ALU.
 template <int D>
-__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], const f32x16 &init,
-                                        f32x16 (&s)[2])
+__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2])
 {
     using C = TileCfg<D>;
     constexpr int HK = C::KSTEPS / 2;
+    const f32x16 init = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
 #define PEVLM_KFRAG(kc, kk) \
     (*reinterpret_cast<const bf16x8 *>(tk + (kc) * 32 * C::ROWB + L.k_row_off + ((((kk) * 2 + L.g32) ^ L.k_swz) << 4)))
@@ -122,17 +119,18 @@ __device__ __forceinline__ float row_max(const f32x16 (&s)[2])
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-// weights p = exp2(s') of the tile, s' being the exponent left by qk_tile: bf16 pairs (B fragments
-// of the value MFMAs), their sum over this lane's 32 keys (dot product of each pair with (1, 1)), and
-// the OR of all pair bit patterns, from which "some weight reached 2^kRescaleStep" is read off.
+// weights p = exp2(c s - m) of the tile (c = scale*log2(e), m = the row's reference maximum in
+// base-2 units): bf16 pairs (B fragments of the value MFMAs), their sum over this lane's 32 keys
+// (dot product of each pair with (1, 1)), and the OR of all pair bit patterns, from which "some
+// weight reached 2^kRescaleStep" is read off.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float &psum, uint32_t &orb)
+__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float c_log2, float mref, float &psum, uint32_t &orb)
 {
     bf16x2 pr;
-    pr[0] = (__bf16)__builtin_amdgcn_exp2f(s0);
-    pr[1] = (__bf16)__builtin_amdgcn_exp2f(s1);
+    pr[0] = (__bf16)__builtin_amdgcn_exp2f(s0 * c_log2 - mref);
+    pr[1] = (__bf16)__builtin_amdgcn_exp2f(s1 * c_log2 - mref);
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
     const uint32_t word = __builtin_bit_cast(uint32_t, pr);
@@ -140,12 +138,12 @@ __device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float &psum,
     return word;
 }
 
-__device__ __forceinline__ void weights(const f32x16 (&s)[2], float &psum, uint32_t &orb, u32x4 (&pf)[4])
+__device__ __forceinline__ void weights(const f32x16 (&s)[2], float c_log2, float mref, float &psum, uint32_t &orb, u32x4 (&pf)[4])
 {
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], psum, orb);
+        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum, orb);
 }
 
 // true when a bf16 pair pattern (or an OR of such patterns of non-negative values) holds a value
@@ -196,8 +194,8 @@ __device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L
 // both pipes of the SIMD run from one instruction stream.  V^T fragments are read one k-step ahead.
 template <int D>
 __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
-                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float &psum,
-                                                    uint32_t &orb, u32x4 (&pf_new)[4])
+                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float c_log2,
+                                                    float mref, float &psum, uint32_t &orb, u32x4 (&pf_new)[4])
 {
     using C = TileCfg<D>;
     constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
@@ -214,7 +212,7 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 #pragma unroll
         for (int e = 0; e < PPM; ++e) {
             const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;
-            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], psum, orb);
+            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum, orb);
         }
         // keep the running values here (plain arithmetic would otherwise be emitted after the last MFMA)
         asm volatile("" : "+v"(psum), "+v"(orb));
@@ -362,36 +360,28 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     asm volatile("" ::: "memory");
-    // Q fragments, multiplied by scale*log2(e) (rounded to bf16 again) so that the score MFMAs
-    // deliver base-2 exponents directly
     const float c_log2 = p.scale * 1.4426950408889634f;
     bf16x8 qf[KSTEPS];
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-        const bf16x8 raw = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
-#pragma unroll
-        for (int j = 0; j < 8; ++j) qf[kk][j] = (__bf16)((float)raw[j] * c_log2);
-    }
+    for (int kk = 0; kk < KSTEPS; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
 
-    // m_ref: reference maximum of this lane's row in base-2 exponent units (-inf: none yet);
-    // neg_ref: sixteen copies of -m_ref (0 while there is none), the start value of the score chains
+    // m_ref: reference maximum of this lane's row in base-2 units, c_log2 * score (-inf: none yet)
     float m_ref = -INFINITY, l_run = 0.f;
-    f32x16 neg_ref;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) neg_ref[i] = 0.f;
+#define PEVLM_MREF ((m_ref == -INFINITY) ? 0.f : m_ref)
     f32x16 o[DBLK];
 #pragma unroll
     for (int b = 0; b < DBLK; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
-    // exponents of tile t -> s (masked where the tile touches the diagonal or the end of its range)
+    // scores of tile t -> s (masked where the tile touches the diagonal or the end of its range)
 #define PEVLM_SCORES(t)                                                                   \
     do {                                                                                  \
         int32_t k0, kend;                                                                 \
         bool causal;                                                                      \
         PEVLM_TILE_RANGE(t, k0, kend, causal);                                            \
-        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, neg_ref, s);                         \
+        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, s);                                 \
         if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo)))                        \
             mask_tile(s, k0, kend, causal, my_row, g32);                                  \
     } while (0)
@@ -403,21 +393,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
 #define PEVLM_FIX_REFERENCE()                                                                         \
     do {                                                                                              \
         if (__any(pair_reached_step(orb) || m_ref == -INFINITY)) {                                    \
-            const float mx = row_max(s);                                                              \
+            const float mx = row_max(s) * c_log2;                                                     \
             const bool has = m_ref != -INFINITY;                                                      \
-            const float shift = has ? fmaxf(mx, 0.f) : (mx == -INFINITY ? 0.f : mx);                  \
-            const float alpha = has ? __builtin_amdgcn_exp2f(-shift) : 1.f;                           \
-            m_ref = has ? m_ref + shift : mx;                                                         \
-            _Pragma("unroll") for (int kc = 0; kc < 2; ++kc)                                          \
-                _Pragma("unroll") for (int i = 0; i < 16; ++i) s[kc][i] -= shift;                     \
+            const float m_new = fmaxf(m_ref, mx);                                                     \
+            const float alpha = has ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;                    \
+            m_ref = m_new;                                                                            \
             psum = 0.f;                                                                               \
             orb = 0u;                                                                                 \
-            weights(s, psum, orb, pf_new);                                                            \
-            l_run *= alpha;                                                                           \
-            _Pragma("unroll") for (int b = 0; b < DBLK; ++b)                                          \
-                _Pragma("unroll") for (int i = 0; i < 16; ++i) o[b][i] *= alpha;                      \
-            const float nr = (m_ref == -INFINITY) ? 0.f : -m_ref;                                     \
-            _Pragma("unroll") for (int i = 0; i < 16; ++i) neg_ref[i] = nr;                           \
+            weights(s, c_log2, PEVLM_MREF, psum, orb, pf_new);                                        \
+            if (__any(has)) { /* rows without a reference have o = l = 0 */                          \
+                l_run *= alpha;                                                                       \
+                _Pragma("unroll") for (int b = 0; b < DBLK; ++b)                                      \
+                    _Pragma("unroll") for (int i = 0; i < 16; ++i) o[b][i] *= alpha;                  \
+            }                                                                                         \
         }                                                                                             \
     } while (0)
 
@@ -429,8 +417,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         PEVLM_TOP(0);
         PEVLM_SCORES(0);
         psum = 0.f;
-        orb = 0u;
-        weights(s, psum, orb, pf_new);
+        orb = 0u;  // no row has a reference yet: the first tile always takes the exact path
         PEVLM_FIX_REFERENCE();
         l_run += psum;
 #pragma unroll
@@ -441,7 +428,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             // values of tile t-1 (matrix cores) under the weights of tile t (vector ALU)
             psum = 0.f;
             orb = 0u;
-            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, psum, orb, pf_new);
+            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, orb, pf_new);
             PEVLM_FIX_REFERENCE();
             l_run += psum;
 #pragma unroll

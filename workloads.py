@@ -33,6 +33,8 @@ class Workload:
     value_scale: float = 1.0
     key_offset_scale: float = 0.0  # std of a per-KV-head mean added to every key (sink skew)
     note: str = ""
+    qk_scale: float = 1.0  # extra factor on Q and K only (peaky softmax)
+    key_ramp: float = 1.0  # keys grow linearly to this factor along each sequence (rising maxima)
 
     @property
     def cu_seqlens(self) -> np.ndarray:
@@ -138,6 +140,10 @@ def generate(w: Workload, seed: int = GLOBAL_SEED) -> Dict[str, np.ndarray]:
                              ("v", TENSOR_V, w.n_kv_heads)):
             x = _rng(w.config_id, si, tid, seed).standard_normal((n, H, D), dtype=np.float32)
             x *= np.float32(w.value_scale)
+            if name in ("q", "k") and w.qk_scale != 1.0:
+                x *= np.float32(w.qk_scale)
+            if name == "k" and w.key_ramp != 1.0:
+                x *= np.linspace(1.0, w.key_ramp, n, dtype=np.float32)[:, None, None]
             if name == "k" and w.key_offset_scale > 0.0:
                 mu = _rng(w.config_id, si, TENSOR_OFFSET, seed).standard_normal((1, H, D), dtype=np.float32)
                 x += mu * np.float32(w.key_offset_scale)
