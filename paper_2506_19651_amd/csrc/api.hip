@@ -124,8 +124,26 @@ static int64_t total_query_rows(const pevlm_layout *lay)
     return n;
 }
 
-// Split count when the caller leaves it to the library: enough workgroups to cover the chip a few
-// times, but no split shorter than a few key tiles.
+// Compute units of the current device (256 when it cannot be queried, e.g. no GPU present).
+static int32_t compute_units()
+{
+    static int32_t cached[16] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) { (void)hipGetLastError(); return 256; }
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// Split count when the caller leaves it to the library: the split kernel keeps two workgroups per
+// compute unit, so the number of workgroups (row tiles x heads x splits) is brought as close as
+// possible to one or two full rounds of 2 x CUs from below, with no split shorter than 512 keys.
 static int32_t auto_splits(const pevlm_layout *lay, const pevlm_heads *h)
 {
     int64_t tiles = count_query_tiles(lay, tile_rows_of(h, true));
@@ -133,8 +151,12 @@ static int32_t auto_splits(const pevlm_layout *lay, const pevlm_heads *h)
     int64_t max_len = 0;
     for (int32_t s = 0; s < lay->num_seqs; ++s)
         max_len = std::max<int64_t>(max_len, (int64_t)lay->cu_seqlens[s + 1] - lay->cu_seqlens[s]);
-    int64_t want = (1024 + tiles * h->n_q_heads - 1) / (tiles * h->n_q_heads);
-    int64_t cap = std::max<int64_t>(1, max_len / 512);
+    const int64_t units = tiles * h->n_q_heads;
+    const int64_t slots = 2 * (int64_t)compute_units();
+    int64_t want = slots / units;                      // one round
+    if (want < 1) want = 1;
+    if (want * units * 4 < slots * 3) want = (2 * slots) / units;  // badly filled round: take two
+    const int64_t cap = std::max<int64_t>(1, max_len / 512);
     return (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, cap), PEVLM_MAX_SPLITS));
 }
 
