@@ -120,8 +120,9 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: sink {w.seqs[0][0]}, {w.seqs[0][2] // w.seqs[0][1]} blocks x {w.seqs[0][1]}, "
-                               f"question {w.seqs[0][3]}, L={T}, {w.n_q_heads}/{w.n_kv_heads} heads x {w.head_dim}",
+        "config": {"workload": f"{w.name}: {len(w.seqs)} sequence(s), sink {w.seqs[0][0]}, blocks of {w.seqs[0][1]} "
+                               f"({', '.join(str(-(-c // b)) for (_s, b, c, _q) in w.seqs)} per sequence), "
+                               f"question {w.seqs[0][3]}, T={T}, {w.n_q_heads}/{w.n_kv_heads} heads x {w.head_dim}",
                    "tokens": T, "num_splits": args.num_splits},
         "ms_per_layer": round(ms_rope + ms_prefill + ms_query, 4),
         "ms_rope": round(ms_rope, 4),

@@ -48,7 +48,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # PEVLM_ORACLE_LIB: load another build of the oracle (the mutation tests plant a mistake in
+        # a copy of the C source and check that the pins notice)
+        _lib = ctypes.CDLL(os.environ.get("PEVLM_ORACLE_LIB") or build())
         _lib.pevlm_oracle_check_layout.restype = ctypes.c_int
         _lib.pevlm_oracle_visible.restype = ctypes.c_int
         _lib.pevlm_oracle_visible.argtypes = [ctypes.c_int64] * 5

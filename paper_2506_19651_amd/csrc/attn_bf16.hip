@@ -222,7 +222,7 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 }
 
 template <int D, bool PARTIAL>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner)
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads)
 {
     using C = TileCfg<D>;
     constexpr int KT = C::KT, ROWB = C::ROWB, CH = C::CH, NLD = C::NLD, KSTEPS = C::KSTEPS, DBLK = C::DBLK;
@@ -241,12 +241,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     const int32_t item_idx = rest % p.n_items;
     const int32_t hs = (rest / p.n_items) * heads_inner + inner;
     const pevlm_work_item it = p.items[item_idx];
-    const int32_t h = p.heads.head_order[hs];
-    const int32_t g = p.heads.kv_of_q[h];
+    const int32_t g = p.heads.kv_of_q[p.heads.head_order[hs]];
     const int32_t Hq = p.n_q_heads, Hkv = p.n_kv_heads;
 
     const int32_t tid = threadIdx.x, lane = tid & 63;
     const int32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Short items (<= 64 rows: small question blocks, tails of context blocks) would leave
+    // wavefronts idle.  When the query heads of a KV group are scheduled next to each other, such an
+    // item is taken for 2 or 4 heads of the group at once (they need the same K/V tiles): wave w
+    // then owns row group w % wph of head slot inner + w / wph, and the workgroups of the other head
+    // slots leave at once.
+    const int32_t groups32 = (it.q_rows + 31) >> 5;
+    const int32_t wph = groups32 <= 1 ? 1 : (groups32 <= 2 ? 2 : 4);  // wavefronts per head
+    const int32_t hpw = pack_heads ? 4 / wph : 1;                     // heads per workgroup
+    if (hpw > 1 && (inner % hpw) != 0) return;
+    const int32_t slot = hpw > 1 ? inner + wave / wph : inner;
+    const bool head_ok = slot < heads_inner;
+    const int32_t h = p.heads.head_order[hs - inner + (head_ok ? slot : inner)];
+    const int32_t rg = hpw > 1 ? wave % wph : wave;  // this wave's group of 32 rows
     const int32_t l32 = lane & 31, g32 = lane >> 5;
     const uint16_t *Q = (const uint16_t *)p.q, *K = (const uint16_t *)p.k, *V = (const uint16_t *)p.v;
 
@@ -259,12 +271,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     L.v_swz = (lane >> 2) & VSW;
 
     // ---- this lane's query row ----
-    const int32_t row_in_tile = wave * 32 + l32;
-    const bool row_valid = row_in_tile < it.q_rows;
-    const int32_t my_row = it.q_start + (row_valid ? row_in_tile : it.q_rows - 1);
-    const bool wave_active = wave * 32 < it.q_rows;
-    const int32_t wr_lo = it.q_start + wave * 32;
-    const int32_t wr_hi = it.q_start + ((wave * 32 + 31 < it.q_rows) ? wave * 32 + 31 : it.q_rows - 1);
+    const int32_t row_in_tile = rg * 32 + l32;
+    const bool row_valid = head_ok && row_in_tile < it.q_rows;
+    const int32_t my_row = it.q_start + (row_in_tile < it.q_rows ? row_in_tile : it.q_rows - 1);
+    const bool wave_active = head_ok && rg * 32 < it.q_rows;
+    const int32_t wr_lo = it.q_start + rg * 32;
+    const int32_t wr_hi = it.q_start + ((rg * 32 + 31 < it.q_rows) ? rg * 32 + 31 : it.q_rows - 1);
 
     const uint32_t lds_k_addr = (uint32_t)(size_t)LDS_PTR(void, lds_k);
     const uint32_t lds_v_addr = (uint32_t)(size_t)LDS_PTR(void, lds_v);
@@ -277,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
 #pragma unroll
     for (int j = 0; j < WSLICE / 1024; ++j) {
         const int32_t rl = j * RPI + lane / CH, cpos = lane % CH;
-        int32_t r = wave * 32 + rl;
+        int32_t r = rg * 32 + rl;
         r = r < it.q_rows ? r : it.q_rows - 1;
         load_lds_16(Q + ((int64_t)(it.q_start + r) * Hq + h) * D + ((cpos ^ (rl & (CH - 1))) << 3),
                     wave_slice_addr + j * 1024);
@@ -497,8 +509,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         for (int j = 0; j < WSLICE / 1024; ++j) {
             const int32_t rl = j * RPI + lane / CH, cpos = lane % CH;
             const uint4 val = *reinterpret_cast<const uint4 *>(oslice + rl * ROWB + ((cpos ^ (rl & (CH - 1))) << 4));
-            if (wave * 32 + rl < it.q_rows)
-                *reinterpret_cast<uint4 *>(obase + ((int64_t)(it.q_start + wave * 32 + rl) * Hq + h) * D + cpos * 8) = val;
+            if (head_ok && rg * 32 + rl < it.q_rows)
+                *reinterpret_cast<uint4 *>(obase + ((int64_t)(it.q_start + rg * 32 + rl) * Hq + h) * D + cpos * 8) = val;
         }
         if (p.lse && g32 == 0 && row_valid) p.lse[(int64_t)my_row * Hq + h] = (m_ref + __log2f(l_tot)) * 0.69314718056f;
     }
@@ -512,14 +524,15 @@ hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStr
     for (int32_t i = 0; i < p.n_q_heads; ++i)
         if (p.heads.kv_of_q[p.heads.head_order[i]] != i / G) uniform = false;
     int32_t heads_inner = uniform ? G : p.n_q_heads;
+    int32_t pack = (uniform && G > 1) ? 1 : 0;  // short items are taken for several heads of a KV group at once
     int32_t n_logical = p.n_items * p.n_q_heads;
     dim3 grid((n_logical + 7) / 8 * 8), block(256);
     if (D == 128) {
-        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, 0, stream, p, n_logical, heads_inner);
-        else hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, 0, stream, p, n_logical, heads_inner);
+        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
+        else hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
     } else {
-        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, 0, stream, p, n_logical, heads_inner);
-        else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, 0, stream, p, n_logical, heads_inner);
+        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
+        else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
     }
     return hipGetLastError();
 }
