@@ -8,8 +8,10 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line:
   roofline   the dominant kernel (block-prefill attention) against the bf16 MFMA peak, its duration
              measured with HIP events on the launch stream inside the timed region
   cpu_baseline  the fp64 CPU oracle timed on a bounded row sample of the same workload
-and, as context, ms per kernel, this build's own dense full-causal attention on the same tokens and
-the resulting attention speedup (the paper reports up to 7.47x on one H20-96G).
+and, as context, ms per kernel (mean, median, min), this build's own dense full-causal attention on
+the same tokens and the resulting attention speedup (the paper reports up to 7.47x on one H20-96G),
+the question kernel with its K/V flushed out of the caches first ("cold"), and what the device
+sustains on a register-resident bf16 MFMA loop and on a 1 GiB streaming copy ("measured_peaks").
 """
 import argparse
 import json
@@ -36,6 +38,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-causal", action="store_true")
     ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-rate / copy / cold-cache side measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this path uses no collectives and every GPU box here has one "
@@ -98,9 +101,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
-    ms_rope = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    ms_prefill = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    ms_query = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    t_rope = np.array([e[0].elapsed_time(e[1]) for e in events])
+    t_prefill = np.array([e[1].elapsed_time(e[2]) for e in events])
+    t_query = np.array([e[2].elapsed_time(e[3]) for e in events])
+    ms_rope, ms_prefill, ms_query = float(t_rope.mean()), float(t_prefill.mean()), float(t_query.mean())
 
     f_prefill, f_query = P.useful_flops(lay, heads)
     T = w.total_tokens
@@ -128,6 +132,9 @@ def main():
         "ms_rope": round(ms_rope, 4),
         "ms_block_prefill": round(ms_prefill, 4),
         "ms_query_attn": round(ms_query, 4),
+        "ms_median_min": {"rope": [round(float(np.median(t_rope)), 4), round(float(t_rope.min()), 4)],
+                          "block_prefill": [round(float(np.median(t_prefill)), 4), round(float(t_prefill.min()), 4)],
+                          "query_attn": [round(float(np.median(t_query)), 4), round(float(t_query.min()), 4)]},
         "block_prefill_useful_tflops": round(f_prefill / (ms_prefill * 1e-3) / 1e12, 2),
         "query_attn_useful_tflops": round(f_query / (ms_query * 1e-3) / 1e12, 2),
         "rope_gbs": round(rope_bytes / (ms_rope * 1e-3) / 1e9, 1),
@@ -143,6 +150,52 @@ def main():
         },
         "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
     }
+
+    if not args.no_probes:
+        # what the device sustains: bf16 MFMA issue (two workgroups per CU, as the attention kernel
+        # runs) and a 1 GiB streaming copy; the copy is also the known-size kernel that scales the
+        # FETCH_SIZE / WRITE_SIZE counters of a profiler pass over this same command
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                fn()
+                b.record(stream)
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return float(np.median(ts))
+
+        scratch = torch.zeros(64, dtype=torch.float32, device=dev)
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        flops = P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream)
+        ms_m = timed(lambda: P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream), 5)
+        gib = 1 << 30
+        src = torch.empty(gib, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty(gib, dtype=torch.uint8, device=dev)
+        ms_c = timed(lambda: P.pevlm_probe_copy(dst, src, gib, stream=stream), 5)
+        mfma_rate = flops / (ms_m * 1e-3) / 1e12
+        copy_rate = 2 * gib / (ms_c * 1e-3) / 1e9
+        result["measured_peaks"] = {"mfma_bf16_tflops": round(mfma_rate, 1), "hbm_copy_gbs": round(copy_rate, 1),
+                                    "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 workgroups/CU; 1 GiB device copy (read+write bytes)"}
+        result["roofline"]["frac_of_measured_mfma_rate"] = round(result["roofline"]["achieved"] / mfma_rate, 4)
+        result["rope_frac_of_measured_copy_rate"] = round(result["rope_gbs"] / copy_rate, 4)
+        # question attention with K/V evicted: the 1 GiB copy (4x the 256 MB last-level cache) runs
+        # right before each timed launch
+        cold = []
+        for _ in range(5):
+            P.pevlm_probe_copy(dst, src, gib, stream=stream)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=args.num_splits, workspace=ws_q, stream=stream)
+            b.record(stream)
+            torch.cuda.synchronize()
+            cold.append(a.elapsed_time(b))
+        result["ms_query_attn_cold"] = round(float(np.median(cold)), 4)
+        result["query_kv_gbs_cold"] = round(kv_bytes / (float(np.median(cold)) * 1e-3) / 1e9, 1)
+        del src, dst
 
     if not args.no_full_causal:
         wf = W.CONFIGS["c3_full_causal"] if args.workload == "c3" else W.small_variant(

@@ -150,6 +150,21 @@ int64_t pevlm_query_worklist_host(const pevlm_layout *layout, int32_t tile_rows,
 pevlm_status pevlm_visible_pairs(const pevlm_layout *layout, int64_t *sink_pairs, int64_t *block_pairs,
                                  int64_t *question_pairs);
 
+/* ---- roofline probes (measurement only; none of the method's arithmetic) ----
+ * The block-prefill kernel is bound by the bf16 matrix cores and the RoPE / question kernels by
+ * HBM (the operation counts of Eq. 6-10 against the bytes of Q, K, V, O).  These two calls let a
+ * benchmark time, on the same device and clocks, what those resources sustain.
+ *
+ * pevlm_probe_mfma_bf16: `workgroups` workgroups of 4 wavefronts each issue 4*iters register-resident
+ * v_mfma_f32_32x32x16_bf16 instructions; *flop_count (HOST, may be NULL) receives the floating-point
+ * operations of the launch.  scratch: DEVICE, >= 4 bytes, never written in practice.
+ * pevlm_probe_copy: streaming copy of `bytes` (multiple of 16) from src to dst (DEVICE, 16-byte
+ * aligned, not overlapping): bytes read + bytes written = 2*bytes.
+ * Both enqueue one kernel on `stream` and return PEVLM_ERR_INVALID_ARG without launching on bad
+ * arguments. */
+pevlm_status pevlm_probe_mfma_bf16(void *scratch, int32_t workgroups, int32_t iters, double *flop_count, void *stream);
+pevlm_status pevlm_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     pevlm_last_error,
     pevlm_prefill_tile_rows,
     pevlm_prefill_worklist_host,
+    pevlm_probe_copy,
+    pevlm_probe_mfma_bf16,
     pevlm_query_attn,
     pevlm_query_tile_rows,
     pevlm_query_workspace_bytes,

@@ -78,6 +78,10 @@ def load_library():
         lib.pevlm_prefill_worklist_host.argtypes = [LP, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_query_worklist_host.restype = ctypes.c_int64
         lib.pevlm_query_worklist_host.argtypes = [LP, i32, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
+        lib.pevlm_probe_mfma_bf16.restype = ctypes.c_int
+        lib.pevlm_probe_mfma_bf16.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+        lib.pevlm_probe_copy.restype = ctypes.c_int
+        lib.pevlm_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.pevlm_visible_pairs.restype = ctypes.c_int
         lib.pevlm_visible_pairs.argtypes = [LP] + [ctypes.POINTER(ctypes.c_int64)] * 3
         _lib = lib
@@ -156,6 +160,17 @@ def _workspace(nbytes: int, like):
 
 def pevlm_last_error() -> str:
     return load_library().pevlm_last_error().decode()
+
+
+def pevlm_probe_mfma_bf16(scratch, workgroups: int, iters: int, stream=None) -> float:
+    """Enqueues the register-resident bf16 MFMA loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().pevlm_probe_mfma_bf16(_ptr(scratch), int(workgroups), int(iters), ctypes.byref(flops), _stream_ptr(stream)))
+    return float(flops.value)
+
+
+def pevlm_probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(load_library().pevlm_probe_copy(_ptr(dst), _ptr(src), int(nbytes), _stream_ptr(stream)))
 
 
 def pevlm_version() -> int:

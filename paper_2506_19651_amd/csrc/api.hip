@@ -415,4 +415,22 @@ pevlm_status pevlm_visible_pairs(const pevlm_layout *layout, int64_t *sink_pairs
     return PEVLM_OK;
 }
 
+pevlm_status pevlm_probe_mfma_bf16(void *scratch, int32_t workgroups, int32_t iters, double *flop_count, void *stream)
+{
+    if (!scratch || ((uintptr_t)scratch & 3)) return fail(PEVLM_ERR_INVALID_ARG, "pevlm_probe_mfma_bf16: scratch must be a 4-byte aligned device pointer");
+    if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+        return fail(PEVLM_ERR_INVALID_ARG, "pevlm_probe_mfma_bf16: workgroups in [1, 2^20], iters in [1, 2^24]");
+    if (flop_count) *flop_count = (double)workgroups * 4.0 * (double)iters * 4.0 * 32768.0;
+    hipError_t e = launch_probe_mfma((float *)scratch, workgroups, iters, (hipStream_t)stream);
+    return e == hipSuccess ? PEVLM_OK : hip_fail(e, "probe_mfma_kernel launch");
+}
+
+pevlm_status pevlm_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15) || bytes == 0 || (bytes & 15) || bytes > ((size_t)1 << 40))
+        return fail(PEVLM_ERR_INVALID_ARG, "pevlm_probe_copy: 16-byte aligned device pointers and a positive multiple of 16 bytes");
+    hipError_t e = launch_probe_copy(dst, src, (int64_t)bytes, (hipStream_t)stream);
+    return e == hipSuccess ? PEVLM_OK : hip_fail(e, "probe_copy_kernel launch");
+}
+
 }  // extern "C"

@@ -120,39 +120,33 @@ __device__ __forceinline__ float row_max(const f32x16 (&s)[2])
 }
 
 // weights p = exp2(c s - m) of the tile (c = scale*log2(e), m = the row's reference maximum in
-// base-2 units): bf16 pairs (B fragments of the value MFMAs), their sum over this lane's 32 keys
-// (dot product of each pair with (1, 1)), and the OR of all pair bit patterns, from which "some
-// weight reached 2^kRescaleStep" is read off.
+// base-2 units): bf16 pairs (B fragments of the value MFMAs) and their sum over this lane's 32 keys
+// (dot product of each pair with (1, 1)).  Weights are non-negative, so a sum below 2^kRescaleStep
+// bounds every one of them; an overflowed or invalid weight makes the sum inf or nan.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float c_log2, float mref, float &psum, uint32_t &orb)
+__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float c_log2, float mref, float &psum)
 {
     bf16x2 pr;
     pr[0] = (__bf16)__builtin_amdgcn_exp2f(s0 * c_log2 - mref);
     pr[1] = (__bf16)__builtin_amdgcn_exp2f(s1 * c_log2 - mref);
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-    const uint32_t word = __builtin_bit_cast(uint32_t, pr);
-    orb |= word;
-    return word;
+    return __builtin_bit_cast(uint32_t, pr);
 }
 
-__device__ __forceinline__ void weights(const f32x16 (&s)[2], float c_log2, float mref, float &psum, uint32_t &orb, u32x4 (&pf)[4])
+__device__ __forceinline__ void weights(const f32x16 (&s)[2], float c_log2, float mref, float &psum, u32x4 (&pf)[4])
 {
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum, orb);
+        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum);
 }
 
-// true when a bf16 pair pattern (or an OR of such patterns of non-negative values) holds a value
-// >= 2^kRescaleStep (also inf / nan)
-__device__ __forceinline__ bool pair_reached_step(uint32_t orb)
-{
-    constexpr uint32_t kBits = 0x3F80u + ((uint32_t)kRescaleStep << 7);  // bf16 pattern of 2^kRescaleStep
-    return (orb >> 16) >= kBits || (orb & 0xFFFFu) >= kBits;
-}
+// true unless this lane's sum of weights proves that all of them stayed below 2^kRescaleStep
+__device__ __forceinline__ bool sum_reached_step(float psum) { return !(psum < 256.f); }
+static_assert(kRescaleStep == 8.f, "sum_reached_step compares with 2^kRescaleStep");
 
 // O^T += V^T P^T for a staged V tile (16 MFMAs per 32 values of head_dim ... 4 k-steps x DBLK blocks)
 template <int D>
@@ -195,7 +189,7 @@ __device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L
 template <int D>
 __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
                                                     f32x16 (&o)[D / 32], const f32x16 (&s)[2], float c_log2,
-                                                    float mref, float &psum, uint32_t &orb, u32x4 (&pf_new)[4])
+                                                    float mref, float &psum, u32x4 (&pf_new)[4])
 {
     using C = TileCfg<D>;
     constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
@@ -212,10 +206,10 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 #pragma unroll
         for (int e = 0; e < PPM; ++e) {
             const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;
-            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum, orb);
+            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum);
         }
         // keep the running values here (plain arithmetic would otherwise be emitted after the last MFMA)
-        asm volatile("" : "+v"(psum), "+v"(orb));
+        asm volatile("" : "+v"(psum));
         if (((n + 1) * PPM) % 4 == 0) asm volatile("" : "+v"(pf_new[((n + 1) * PPM) / 4 - 1]));
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -398,21 +392,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             mask_tile(s, k0, kend, causal, my_row, g32);                                  \
     } while (0)
     // The weights of a tile are first formed against the reference maximum the row already has.
-    // Only if some weight reached 2^kRescaleStep (or a row has no reference yet) is the row maximum
-    // of the tile computed, the reference raised, o and l scaled down and the tile's weights formed
+    // Only if a lane's weights may have reached 2^kRescaleStep (or a row has no reference yet) is the
+    // row maximum of the tile computed, the reference raised, o and l scaled down and the tile's weights formed
     // again: weights stay below 2^kRescaleStep, which fp32 sums and bf16 weights carry without loss,
     // and on almost every tile the vector ALU only does exp2, convert and sum.
 #define PEVLM_FIX_REFERENCE()                                                                         \
     do {                                                                                              \
-        if (__any(pair_reached_step(orb) || m_ref == -INFINITY)) {                                    \
+        if (__any(sum_reached_step(psum) || m_ref == -INFINITY)) {                                    \
             const float mx = row_max(s) * c_log2;                                                     \
             const bool has = m_ref != -INFINITY;                                                      \
             const float m_new = fmaxf(m_ref, mx);                                                     \
             const float alpha = has ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;                    \
             m_ref = m_new;                                                                            \
             psum = 0.f;                                                                               \
-            orb = 0u;                                                                                 \
-            weights(s, c_log2, PEVLM_MREF, psum, orb, pf_new);                                        \
+            weights(s, c_log2, PEVLM_MREF, psum, pf_new);                                             \
             if (__any(has)) { /* rows without a reference have o = l = 0 */                          \
                 l_run *= alpha;                                                                       \
                 _Pragma("unroll") for (int b = 0; b < DBLK; ++b)                                      \
@@ -424,12 +417,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     f32x16 s[2];
     u32x4 pf_prev[4], pf_new[4];
     float psum;
-    uint32_t orb;
     if (n_w > 0) {
         PEVLM_TOP(0);
         PEVLM_SCORES(0);
-        psum = 0.f;
-        orb = 0u;  // no row has a reference yet: the first tile always takes the exact path
+        psum = 0.f;  // no row has a reference yet: the first tile always takes the exact path
         PEVLM_FIX_REFERENCE();
         l_run += psum;
 #pragma unroll
@@ -439,8 +430,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
             PEVLM_SCORES(t);
             // values of tile t-1 (matrix cores) under the weights of tile t (vector ALU)
             psum = 0.f;
-            orb = 0u;
-            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, orb, pf_new);
+            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, pf_new);
             PEVLM_FIX_REFERENCE();
             l_run += psum;
 #pragma unroll

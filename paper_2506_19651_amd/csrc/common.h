@@ -162,6 +162,8 @@ hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);
+hipError_t launch_probe_mfma(float *sink, int32_t workgroups, int32_t iters, hipStream_t stream);
+hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t stream);
 
 constexpr int32_t kTileRowsF32 = 16;   // query rows per work item of the fp32 kernels
 constexpr int32_t kTileRowsBf16 = 128; // query rows per work item of the bf16 MFMA kernels

@@ -214,3 +214,22 @@ def test_bf16_full_size_sampled_rows(oracle, name, n_random):
     assert torch.isfinite(out.float()).all()
     vmax = float(to_host_f32(r["v"].float().abs().max()))
     assert float(out.float().abs().max()) <= vmax * 1.01
+
+
+def test_roofline_probes_run_and_copy_is_exact():
+    """The measurement-only entry points: the copy moves every byte, the MFMA loop reports its
+    operation count, bad arguments are rejected before any launch."""
+    n = (1 << 20) + 4096
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros_like(src)
+    P.pevlm_probe_copy(dst, src, n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    scratch = torch.zeros(16, dtype=torch.float32, device=DEV)
+    flops = P.pevlm_probe_mfma_bf16(scratch, 8, 10)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 10 * 4 * 32768 and float(scratch.abs().sum()) == 0.0
+    with pytest.raises(P.PevlmError):
+        P.pevlm_probe_copy(dst, src, 24)
+    with pytest.raises(P.PevlmError):
+        P.pevlm_probe_mfma_bf16(scratch, 0, 10)
