@@ -39,12 +39,23 @@ struct LaneOff {
     int32_t k_row_off, k_swz, v_row_off, v_ch_lo, v_swz, g32;
 };
 
+// Global->LDS loads a wavefront slips between the MFMAs of a tile (its share of the next K tile
+// during the score MFMAs, of the current V tile during the value MFMAs): a wavefront-uniform base
+// address, per-lane byte offsets and the LDS address of the wave's first 1 KB piece.
+template <int NLD>
+struct TileLoads {
+    const void *base;
+    uint32_t off[NLD];
+    uint32_t lds;
+};
+
 constexpr float kRescaleStep = 8.f;  // log2 units the row maximum may outgrow the reference maximum
 
 // S^T = K Q^T for the 64 keys of a staged tile: two independent accumulation chains (one per
 // 32-key chunk) issued alternately; A fragments (16 bytes per lane) are fetched half a tile ahead.
-template <int D>
-__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2])
+template <int D, bool LOADS>
+__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2],
+                                        const TileLoads<D / 32> &ld)
 {
     using C = TileCfg<D>;
     constexpr int HK = C::KSTEPS / 2;
@@ -74,6 +85,10 @@ __device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, con
     for (int kk = HK; kk < C::KSTEPS; ++kk) {
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
+        if (LOADS) {  // one 1 KB piece of the next K tile per pair of MFMAs
+            load_lds_16_base(ld.base, ld.off[kk - HK], ld.lds + (kk - HK) * 4096);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 #undef PEVLM_KFRAG
 }
@@ -95,16 +110,20 @@ __device__ __forceinline__ void read_v(const uint8_t *tv, const LaneOff &L, int 
         }
 }
 
-// entries a row must not see: beyond the key range, or (causal range) keys after the row
+// entries a row must not see: beyond the key range, or (causal range) keys after the row.  Key
+// k0 + c is visible iff c <= min(kend - 1, causal ? my_row : inf) - k0; c = const + 4*g32 per entry,
+// so each entry costs one compare against a per-lane limit and one select.
 __device__ __forceinline__ void mask_tile(f32x16 (&s)[2], int32_t k0, int32_t kend, bool causal, int32_t my_row, int32_t g32)
 {
+    int32_t last = kend - 1;
+    if (causal) last = my_row < last ? my_row : last;
+    const int32_t lim = last - k0 - g32 * 4;
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int32_t key = k0 + kc * 32 + (i >> 2) * 8 + g32 * 4 + (i & 3);
-            const bool ok = key < kend && (!causal || key <= my_row);
-            s[kc][i] = ok ? s[kc][i] : -INFINITY;
+            const int32_t c = kc * 32 + (i >> 2) * 8 + (i & 3);
+            s[kc][i] = c <= lim ? s[kc][i] : -INFINITY;
         }
 }
 
@@ -189,7 +208,7 @@ __device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L
 template <int D>
 __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
                                                     f32x16 (&o)[D / 32], const f32x16 (&s)[2], float c_log2,
-                                                    float mref, float &psum, u32x4 (&pf_new)[4])
+                                                    float mref, float &psum, u32x4 (&pf_new)[4], const TileLoads<D / 32> &ld)
 {
     using C = TileCfg<D>;
     constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
@@ -203,6 +222,7 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
         const int ks = n / C::DBLK, b = n % C::DBLK;
         if (ks + 1 < 4) vf[(ks + 1) & 1][b] = read_v_one<D>(tv_prev, L, ks + 1, b);
         o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1][b], __builtin_bit_cast(bf16x8, pf_prev[ks]), o[b], 0, 0, 0);
+        if (n % 4 == 0) load_lds_16_base(ld.base, ld.off[n / 4], ld.lds + (n / 4) * 4096);  // a piece of the current V tile
 #pragma unroll
         for (int e = 0; e < PPM; ++e) {
             const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;
@@ -232,7 +252,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     if (logical >= n_logical) return;
     const int32_t inner = logical % heads_inner;
     const int32_t rest = logical / heads_inner;
-    const int32_t item_idx = rest % p.n_items;
+    // last item first: within a context block the later tiles are the longer ones, and a launch that
+    // ends on short items has a shorter tail
+    const int32_t item_idx = p.n_items - 1 - rest % p.n_items;
     const int32_t hs = (rest / p.n_items) * heads_inner + inner;
     const pevlm_work_item it = p.items[item_idx];
     const int32_t g = p.heads.kv_of_q[p.heads.head_order[hs]];
@@ -359,6 +381,32 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         PEVLM_ISSUE_V(t);                                              \
     } while (0)
 
+    // Inside the pipelined loop the loads of a tile are not issued in one burst behind the barrier
+    // (the wavefront would sit in the memory-instruction queue while its MFMAs wait) but one at a
+    // time between MFMAs.  PEVLM_SET_LOADS prepares them: base address of tile tl, LDS destination in
+    // `stage`, and, for a tile that runs past the end of its key range, per-lane offsets clamped to
+    // the last valid key (put back to the plain ones on the next use).
+#define PEVLM_SET_LOADS(ld, T, toff, modified, swz_expr, lds_base_addr, tl, stage)                      \
+    do {                                                                                              \
+        int32_t pk0, pkend;                                                                           \
+        bool pcausal;                                                                                 \
+        PEVLM_TILE_RANGE(tl, pk0, pkend, pcausal);                                                    \
+        (void)pcausal;                                                                                \
+        const bool edge = pk0 + KT > pkend;                                                           \
+        if (edge || modified) {                                                                       \
+            const int32_t last = edge ? pkend - 1 - pk0 : KT - 1;                                     \
+            _Pragma("unroll") for (int j = 0; j < NLD; ++j) {                                         \
+                const int32_t row = (j * 4 + wave) * RPI + lane / CH, cpos = lane % CH;               \
+                const int32_t key = row < last ? row : last;                                          \
+                toff[j] = (uint32_t)((key * Hkv * D + ((cpos ^ (swz_expr)) << 3)) * 2);               \
+            }                                                                                         \
+            modified = edge;                                                                          \
+        }                                                                                             \
+        ld.base = uniform_ptr(T + ((int64_t)pk0 * Hkv + g) * D);                                      \
+        ld.lds = lds_base_addr + (stage) * TILEB + wave * 1024;                                       \
+        _Pragma("unroll") for (int j = 0; j < NLD; ++j) ld.off[j] = toff[j];                          \
+    } while (0)
+
     if (n_tiles > 0) {
         PEVLM_ISSUE_K(0);
         __builtin_amdgcn_s_waitcnt(0x0F70 | NLD);  // all but the K(0) loads: Q has landed
@@ -382,12 +430,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
 
     // scores of tile t -> s (masked where the tile touches the diagonal or the end of its range)
-#define PEVLM_SCORES(t)                                                                   \
+#define PEVLM_SCORES(t, LOADS)                                                            \
     do {                                                                                  \
         int32_t k0, kend;                                                                 \
         bool causal;                                                                      \
         PEVLM_TILE_RANGE(t, k0, kend, causal);                                            \
-        qk_tile<D>(lds_k + ((t) & 1) * TILEB, L, qf, s);                                 \
+        qk_tile<D, LOADS>(lds_k + ((t) & 1) * TILEB, L, qf, s, ldk);                     \
         if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo)))                        \
             mask_tile(s, k0, kend, causal, my_row, g32);                                  \
     } while (0)
@@ -417,24 +465,48 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     f32x16 s[2];
     u32x4 pf_prev[4], pf_new[4];
     float psum;
+    TileLoads<NLD> ldk, ldv;
+    bool k_mod = false, v_mod = false;
     if (n_w > 0) {
         PEVLM_TOP(0);
-        PEVLM_SCORES(0);
+        PEVLM_SCORES(0, false);
         psum = 0.f;  // no row has a reference yet: the first tile always takes the exact path
         PEVLM_FIX_REFERENCE();
         l_run += psum;
 #pragma unroll
         for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
         for (int32_t t = 1; t < n_w; ++t) {
-            PEVLM_TOP(t);
-            PEVLM_SCORES(t);
+            // top of tile t as in PEVLM_TOP, but K(t+1) and V(t) are fetched piecewise between the
+            // MFMAs below; after the last tile the K loads repeat that tile into the stage nobody
+            // reads any more, which keeps the loop body free of branches
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            const int32_t tk = t + 1 < n_tiles ? t + 1 : n_tiles - 1;
+            PEVLM_SET_LOADS(ldk, K, koff, k_mod, (row & (CH - 1)), lds_k_addr, tk, (t + 1) & 1);
+            PEVLM_SET_LOADS(ldv, V, voff, v_mod, ((row & VSW) << 2), lds_v_addr, t, t & 1);
+            PEVLM_SCORES(t, true);
             // values of tile t-1 (matrix cores) under the weights of tile t (vector ALU)
             psum = 0.f;
-            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, pf_new);
+            pv_prev_weights_cur<D>(lds_v + ((t - 1) & 1) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, pf_new, ldv);
             PEVLM_FIX_REFERENCE();
             l_run += psum;
 #pragma unroll
             for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
+        }
+    }
+    // the burst loads below use the plain per-lane offsets
+    if (k_mod) {
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int32_t row = (j * 4 + wave) * RPI + lane / CH, cpos = lane % CH;
+            koff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ (row & (CH - 1))) << 3)) * 2);
+        }
+    }
+    if (v_mod) {
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int32_t row = (j * 4 + wave) * RPI + lane / CH, cpos = lane % CH;
+            voff[j] = (uint32_t)((row * Hkv * D + ((cpos ^ ((row & VSW) << 2)) << 3)) * 2);
         }
     }
     // Every wavefront passes the top of all n_tiles tiles and one final barrier.  The values of the
