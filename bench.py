@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # HBM bytes per block-prefill launch from the FETCH_SIZE / WRITE_SIZE passes recorded in
 # profiles/attn_bf16_prefill_c3_counters.md (scaled by the same counters on a 1 GiB device copy)
-MEASURED_PREFILL_TRAFFIC_BYTES = {"c3": 1.081e9}
+MEASURED_PREFILL_TRAFFIC_BYTES = {"c3": 1.095e9}
 HBM_PEAK_GBS = 8000.0
 
 
