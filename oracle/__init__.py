@@ -12,6 +12,7 @@ from .pevlm_oracle import (  # noqa: F401
     mask_matrix,
     visible,
     rope,
+    rope_mrope,
     attn,
     forward,
     threads,

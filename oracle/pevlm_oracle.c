@@ -172,6 +172,41 @@ void pevlm_oracle_rope(const void *x, int dtype, int64_t T, int32_t H, int32_t D
 }
 
 /*
+ * Multimodal rotary embedding with three position axes (the position scheme of the Qwen2.5-VL
+ * models the paper evaluates, Sec. "Experimental setup" / related work on 3D-MRoPE; the paper's
+ * rule is only that the original ids are kept, never re-based per block, Sec. "Position Encoding").
+ * The D/2 pair indices are cut into three consecutive sections of section[0], section[1],
+ * section[2] indices (temporal, height, width; they must add up to D/2); pair i of token t turns by
+ *   theta_i = pos3[axis(i)][t] * base^(-2i/D)
+ * with the same rotate-half pairing (i, i + D/2) as pevlm_oracle_rope.  pos3 is [3][T].
+ * With the three axes equal this is pevlm_oracle_rope.
+ */
+void pevlm_oracle_rope_mrope(const void *x, int dtype, int64_t T, int32_t H, int32_t D,
+                             const int32_t *pos3, const int32_t *section, double rope_base,
+                             const int64_t *rows, int64_t n_rows, double *out)
+{
+    if (!rows) n_rows = T;
+    int32_t half = D / 2;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t t = rows ? rows[r] : r;
+        for (int32_t h = 0; h < H; ++h) {
+            int64_t in0 = (t * H + h) * (int64_t)D;
+            double *o = out + (r * H + h) * (int64_t)D;
+            for (int32_t i = 0; i < half; ++i) {
+                int axis = i < section[0] ? 0 : (i < section[0] + section[1] ? 1 : 2);
+                double p_axis = (double)pos3[(int64_t)axis * T + t];
+                double angle = p_axis * pow(rope_base, -(2.0 * i) / D);
+                double ca = cos(angle), sa = sin(angle);
+                double lo = widen(x, dtype, in0 + i), hi = widen(x, dtype, in0 + half + i);
+                o[i] = lo * ca - hi * sa;
+                o[half + i] = hi * ca + lo * sa;
+            }
+        }
+    }
+}
+
+/*
  * Masked softmax attention, Eq. 1 with the explicit PEVLM mask added to the scores:
  *   s_j = (q_i . k_j) / sqrt(D) + M[i][j],  w_j = exp(s_j - max_j s_j),  o_i = sum_j w_j v_j / sum_j w_j
  * for every selected packed row t = rows[r] and every query head h (KV head kv_head_of_q[h]).

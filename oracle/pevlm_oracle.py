@@ -60,6 +60,7 @@ def _load():
         _lib.pevlm_oracle_mask_row.restype = None
         _lib.pevlm_oracle_positions.restype = None
         _lib.pevlm_oracle_rope.restype = None
+        _lib.pevlm_oracle_rope_mrope.restype = None
         _lib.pevlm_oracle_attn.restype = None
     return _lib
 
@@ -159,6 +160,24 @@ def rope(x: np.ndarray, pos: np.ndarray, rope_base: float, rows=None) -> np.ndar
                               ctypes.c_int64(T), ctypes.c_int32(H), ctypes.c_int32(D),
                               pos.ctypes.data_as(ctypes.c_void_p), ctypes.c_double(rope_base),
                               rp, ctypes.c_int64(n), out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def rope_mrope(x: np.ndarray, pos3: np.ndarray, section, rope_base: float, rows=None) -> np.ndarray:
+    """Rotate x[T, H, D] with three position axes pos3[3, T]; pair indices are split into
+    section = (temporal, height, width) consecutive groups.  Returns fp64 [n_rows, H, D]."""
+    x = np.ascontiguousarray(x)
+    T, H, D = x.shape
+    pos3 = np.ascontiguousarray(pos3, dtype=np.int32)
+    sec = np.ascontiguousarray(section, dtype=np.int32)
+    assert pos3.shape == (3, T) and sec.shape == (3,) and int(sec.sum()) == D // 2 and (sec >= 0).all()
+    r, rp, n = _rows_arg(rows, T)
+    out = np.empty((n, H, D), dtype=np.float64)
+    _load().pevlm_oracle_rope_mrope(x.ctypes.data_as(ctypes.c_void_p), ctypes.c_int(_dtype_code(x)),
+                                    ctypes.c_int64(T), ctypes.c_int32(H), ctypes.c_int32(D),
+                                    pos3.ctypes.data_as(ctypes.c_void_p), sec.ctypes.data_as(ctypes.c_void_p),
+                                    ctypes.c_double(rope_base), rp, ctypes.c_int64(n),
+                                    out.ctypes.data_as(ctypes.c_void_p))
     return out
 
 

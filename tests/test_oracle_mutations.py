@@ -25,6 +25,11 @@ MUTATIONS = [
     ("softmax_not_normalised", "for (int32_t d = 0; d < D; ++d) o[d] /= l;", "for (int32_t d = 0; d < D; ++d) o[d] /= (l + 1e-3);"),
     ("value_index", "int64_t v0 = (j * Hkv + g) * (int64_t)D;", "int64_t v0 = (j * Hkv + (Hkv - 1 - g)) * (int64_t)D;"),
     ("lse_dropped_log", "lse[r * Hq + h] = m + log(l);", "lse[r * Hq + h] = m;"),
+    ("mrope_section_boundary", "int axis = i < section[0] ? 0 :", "int axis = i <= section[0] ? 0 :"),
+    ("mrope_axes_swapped", "(i < section[0] + section[1] ? 1 : 2);", "(i < section[0] + section[1] ? 2 : 1);"),
+    ("mrope_sign", "o[i] = lo * ca - hi * sa;", "o[i] = lo * ca + hi * sa;"),
+    ("mrope_frequency_restarts_per_section", "double angle = p_axis * pow(rope_base, -(2.0 * i) / D);",
+     "double angle = p_axis * pow(rope_base, -(2.0 * (i - (axis == 0 ? 0 : axis == 1 ? section[0] : section[0] + section[1]))) / D);"),
 ]
 
 

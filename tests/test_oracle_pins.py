@@ -2,6 +2,7 @@
 the oracle -- brute-force loops over the three formulas (Eq. 3-5), torch's CPU attention routine,
 the paper's closed-form operation counts (Eq. 6-10), closed forms and analytic identities."""
 import itertools
+import cmath
 import math
 
 import numpy as np
@@ -333,6 +334,91 @@ def test_p7_constant_position_offset_changes_nothing(oracle):
     a, _ = oracle.forward(q, k, v, lay, 1.0e4)
     b, _ = oracle.forward(q, k, v, lay, 1.0e4, pos_offset=[1234, 77])
     assert np.max(np.abs(a - b)) <= 1e-9
+
+
+# ------------------------------------------------------------------ multimodal RoPE (three axes)
+def brute_mrope_complex(x, pos3, section, base):
+    """Independent evaluation: pair (i, i+D/2) as one complex number, turned by exp(j * angle), the
+    angle taken from the axis whose consecutive section holds pair index i."""
+    T, H, D = x.shape
+    half = D // 2
+    bounds = np.cumsum([0] + list(section))
+    out = np.empty((T, H, D), dtype=np.float64)
+    for t in range(T):
+        for i in range(half):
+            axis = [a for a in range(3) if bounds[a] <= i < bounds[a + 1]][0]
+            w = cmath.exp(1j * float(pos3[axis][t]) * base ** (-2.0 * i / D))
+            for h in range(H):
+                z = complex(x[t, h, i], x[t, h, i + half]) * w
+                out[t, h, i], out[t, h, i + half] = z.real, z.imag
+    return out
+
+
+def test_p11_mrope_against_brute_force_and_1d_rope(oracle):
+    T, H, D, base = 11, 2, 16, 1.0e4
+    x = RNG.standard_normal((T, H, D))
+    pos3 = np.stack([RNG.integers(0, 3000, T), RNG.integers(0, 40, T), RNG.integers(0, 40, T)]).astype(np.int32)
+    for section in [(2, 3, 3), (8, 0, 0), (0, 0, 8), (1, 6, 1), (3, 5, 0)]:
+        y = oracle.rope_mrope(x, pos3, section, base)
+        np.testing.assert_allclose(y, brute_mrope_complex(x, pos3, section, base), atol=1e-11, rtol=0)
+    # three equal axes: the one-dimensional rotation (pinned above), bit for bit
+    p = pos3[0]
+    np.testing.assert_array_equal(oracle.rope_mrope(x, np.stack([p, p, p]), (2, 3, 3), base), oracle.rope(x, p, base))
+    # rows subset
+    rows = np.array([7, 0, 3], dtype=np.int64)
+    np.testing.assert_array_equal(oracle.rope_mrope(x, pos3, (2, 3, 3), base, rows=rows),
+                                  oracle.rope_mrope(x, pos3, (2, 3, 3), base)[rows])
+
+
+def test_p11_mrope_axis_touches_only_its_section_and_is_relative_per_axis(oracle):
+    T, H, D, base = 6, 2, 32, 1.0e6
+    half, section = D // 2, (4, 6, 6)
+    x = RNG.standard_normal((T, H, D))
+    pos3 = np.stack([np.arange(T) + 5, np.arange(T) % 3, (np.arange(T) * 2) % 5]).astype(np.int32)
+    y = oracle.rope_mrope(x, pos3, section, base)
+    for axis, (lo, hi) in enumerate(((0, 4), (4, 10), (10, 16))):
+        moved = pos3.copy()
+        moved[axis] += 17
+        z = oracle.rope_mrope(x, moved, section, base)
+        idx = np.zeros(D, bool)
+        idx[lo:hi] = True
+        idx[half + lo:half + hi] = True
+        np.testing.assert_array_equal(z[..., ~idx], y[..., ~idx])      # other sections untouched, exactly
+        assert np.all(np.abs(z[..., idx] - y[..., idx]).max(axis=(1, 2)) > 1e-3)
+    # pair norms kept; pair 0 (temporal) turns by exactly pos_t radians
+    np.testing.assert_allclose(y[..., :half] ** 2 + y[..., half:] ** 2, x[..., :half] ** 2 + x[..., half:] ** 2, rtol=1e-13)
+    th = float(pos3[0][2])
+    np.testing.assert_allclose(y[2, :, 0], x[2, :, 0] * math.cos(th) - x[2, :, half] * math.sin(th), atol=1e-14)
+    # first pair of the height section: frequency index continues (i = 4), it does not restart at 0
+    th = float(pos3[1][4]) * base ** (-2.0 * 4 / D)
+    np.testing.assert_allclose(y[4, :, 4], x[4, :, 4] * math.cos(th) - x[4, :, half + 4] * math.sin(th), atol=1e-14)
+    # <R_m q, R_n k> depends on m - n per axis: shift both tokens by the same (dt, dh, dw)
+    qv, kv = RNG.standard_normal((1, 1, D)), RNG.standard_normal((1, 1, D))
+    dots = []
+    for shift in ((0, 0, 0), (900, 3, 11), (50000, 20, 0)):
+        pq = np.array([[10 + shift[0]], [2 + shift[1]], [7 + shift[2]]], np.int32)
+        pk = np.array([[4 + shift[0]], [5 + shift[1]], [1 + shift[2]]], np.int32)
+        dots.append(float(np.sum(oracle.rope_mrope(qv, pq, section, base) * oracle.rope_mrope(kv, pk, section, base))))
+    assert max(dots) - min(dots) <= 1e-9
+
+
+def test_p11_mrope_position_ids_of_a_video_prompt():
+    """The input recipe: text counts on all axes, frames share a temporal id per frame and walk the
+    grid on the other two, the counter resumes after the largest id, nothing restarts per block."""
+    import workloads as W
+    w = W.Workload("m", 9, "f32", 2, 1, 16, 1.0e4, [(10, 8, 20, 3), (2, 4, 5, 2)], 1.0)
+    ids = W.mrope_position_ids(w, frame_tokens=6, grid_w=3)
+    # sequence 0: 4 text tokens, then 26 video tokens = 4 frames of 2x3 + 2 tokens, then 3 text tokens
+    np.testing.assert_array_equal(ids[:, :4], np.tile(np.arange(4), (3, 1)))
+    np.testing.assert_array_equal(ids[0, 4:30], 4 + np.arange(26) // 6)
+    np.testing.assert_array_equal(ids[1, 4:30], 4 + (np.arange(26) % 6) // 3)
+    np.testing.assert_array_equal(ids[2, 4:30], 4 + (np.arange(26) % 6) % 3)
+    np.testing.assert_array_equal(ids[:, 30:33], np.tile(9 + np.arange(3), (3, 1)))  # largest id was 4 + 4
+    # sequence 1 (sink shorter than a frame: all text) starts again from 0
+    np.testing.assert_array_equal(ids[:, 33:35], np.tile(np.arange(2), (3, 1)))
+    np.testing.assert_array_equal(ids[0, 35:40], 2 + np.arange(5) // 6)
+    np.testing.assert_array_equal(ids[2, 35:40], 2 + np.arange(5) % 3)
+    np.testing.assert_array_equal(ids[:, 40:42], np.tile(5 + np.arange(2), (3, 1)))  # largest id was 2 + 2 (column)
 
 
 # ------------------------------------------------------------------ log-sum-exp merge identity

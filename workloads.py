@@ -155,6 +155,39 @@ def as_float32(a: np.ndarray) -> np.ndarray:
     return a if a.dtype == np.float32 else bf16_bits_to_f32(a)
 
 
+# ----------------------------------------------------------------------------- 3-axis position ids
+def mrope_position_ids(w: Workload, frame_tokens: int, grid_w: int) -> np.ndarray:
+    """Three-axis (temporal, height, width) position ids [3, T] of a video prompt, an INPUT of the
+    multimodal-RoPE call (no rotation arithmetic here).  Each sequence is read as: text prefix
+    (the sink minus its last `frame_tokens` tokens, if it is that long), then video frames of
+    `frame_tokens` tokens laid out row-major on a grid `grid_w` wide (end of sink + all context
+    tokens; a trailing partial frame is a truncated grid), then the question as text.  A text token
+    takes the running counter on all three axes; a run of frames that starts at counter n0 gives
+    frame f, row r, column c the ids (n0 + f, n0 + r, n0 + c); the counter then continues after the
+    largest id used.  Ids are those of the whole prompt: nothing restarts at a block boundary."""
+    ids = np.zeros((3, w.total_tokens), dtype=np.int32)
+    t0 = 0
+    for (S, _B, C, Q) in w.seqs:
+        n_text = S - frame_tokens if S >= frame_tokens else S
+        n_video = (S - n_text) + C
+        n = 0
+        ids[:, t0:t0 + n_text] = np.arange(n_text, dtype=np.int32)[None, :]
+        n += n_text
+        if n_video > 0:
+            j = np.arange(n_video, dtype=np.int32)
+            f, rem = j // frame_tokens, j % frame_tokens
+            r, c = rem // grid_w, rem % grid_w
+            v0 = t0 + n_text
+            ids[0, v0:v0 + n_video] = n + f
+            ids[1, v0:v0 + n_video] = n + r
+            ids[2, v0:v0 + n_video] = n + c
+            n += int(max(f.max(), r.max(), c.max())) + 1
+        q0 = t0 + S + C
+        ids[:, q0:q0 + Q] = n + np.arange(Q, dtype=np.int32)[None, :]
+        t0 += S + C + Q
+    return ids
+
+
 # ----------------------------------------------------------------------------- row samples
 def sample_rows(w: Workload, n_random: int = 512, tile: int = 128, seed: int = GLOBAL_SEED,
                 max_question_rows: Optional[int] = None) -> np.ndarray:
