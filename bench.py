@@ -196,6 +196,14 @@ def main():
         result["ms_query_attn_cold"] = round(float(np.median(cold)), 4)
         result["query_kv_gbs_cold"] = round(kv_bytes / (float(np.median(cold)) * 1e-3) / 1e9, 1)
         del src, dst
+        # three-axis RoPE on the same tensors (ids of a video prompt with 16x16 / 14x14 tokens per frame)
+        ft, gw = (196, 14) if w.seqs[0][1] % 196 == 0 else (256, 16)
+        ids = torch.from_numpy(W.mrope_position_ids(w, ft, gw)).to(dev)
+        half = w.head_dim // 2
+        sec = (half // 4, (half - half // 4) // 2, half - half // 4 - (half - half // 4) // 2)
+        ms_mr = timed(lambda: P.pevlm_rope_mrope(q, k, T, heads, w.rope_base, ids, sec, stream=stream), 10)
+        result["ms_rope_mrope"] = round(ms_mr, 4)
+        result["rope_mrope_gbs"] = round((rope_bytes + 12 * T) / (ms_mr * 1e-3) / 1e9, 1)
 
     if not args.no_full_causal:
         wf = W.CONFIGS["c3_full_causal"] if args.workload == "c3" else W.small_variant(

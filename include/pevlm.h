@@ -86,6 +86,22 @@ pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const 
                             double rope_base, const int32_t *pos_offset, void *stream);
 
 /*
+ * Multimodal RoPE with three position axes (temporal, height, width): the position scheme of the
+ * Qwen2.5-VL models the paper evaluates (Sec. "Experimental setup"; related work on 3D-MRoPE).  The
+ * method's rule (Sec. "Position Encoding") is unchanged: the ids are those of the whole prompt and
+ * are never re-based per block, so the caller passes them explicitly.
+ *   pos_ids : DEVICE int32 [3][num_tokens] (axis-major), read by the kernel on `stream`
+ *   section : HOST int32 [3], how many of the head_dim/2 pair indices each axis owns, in the order
+ *             temporal, height, width; consecutive ranges; must add up to head_dim/2
+ * Pair (x[i], x[i+D/2]) of token t turns by pos_ids[axis(i)][t] * rope_base^(-2i/D); in place on
+ * q [num_tokens][Hq][D] and k [num_tokens][Hkv][D] (either may be NULL).  With three equal axes the
+ * result is that of pevlm_rope_seq at those positions.  No layout is needed: sequences only matter
+ * through the ids.
+ */
+pevlm_status pevlm_rope_mrope(void *q, void *k, int64_t num_tokens, const pevlm_heads *heads, double rope_base,
+                              const int32_t *pos_ids, const int32_t *section, void *stream);
+
+/*
  * Block-parallel prefill attention: rows of the sink (Eq. 3) and of every context block (Eq. 4).
  * q and k must already be rotated.  Writes out rows of the sink and context regions only;
  * question rows of `out` (and `lse`) are left untouched.  lse: DEVICE fp32 [T][Hq] natural-log

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     pevlm_query_tile_rows,
     pevlm_query_workspace_bytes,
     pevlm_query_worklist_host,
+    pevlm_rope_mrope,
     pevlm_rope_seq,
     pevlm_version,
     pevlm_visible_pairs,

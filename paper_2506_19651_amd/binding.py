@@ -78,6 +78,8 @@ def load_library():
         lib.pevlm_prefill_worklist_host.argtypes = [LP, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_query_worklist_host.restype = ctypes.c_int64
         lib.pevlm_query_worklist_host.argtypes = [LP, i32, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
+        lib.pevlm_rope_mrope.restype = ctypes.c_int
+        lib.pevlm_rope_mrope.argtypes = [vp, vp, ctypes.c_int64, HP, ctypes.c_double, vp, ctypes.POINTER(ctypes.c_int32), vp]
         lib.pevlm_probe_mfma_bf16.restype = ctypes.c_int
         lib.pevlm_probe_mfma_bf16.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
         lib.pevlm_probe_copy.restype = ctypes.c_int
@@ -190,6 +192,13 @@ def pevlm_rope_seq(q, k, layout: Layout, heads: Heads, rope_base: float, pos_off
     offp = None if off is None else off.ctypes.data_as(ctypes.c_void_p)
     _check(load_library().pevlm_rope_seq(_ptr(q), _ptr(k), layout.ref(), heads.ref(), float(rope_base), offp,
                                          _stream_ptr(stream)))
+
+
+def pevlm_rope_mrope(q, k, num_tokens: int, heads: Heads, rope_base: float, pos_ids, section, stream=None):
+    """pos_ids: device int32 tensor [3, num_tokens]; section: three host ints adding up to head_dim/2."""
+    sec = (ctypes.c_int32 * 3)(*[int(x) for x in section])
+    _check(load_library().pevlm_rope_mrope(_ptr(q), _ptr(k), int(num_tokens), heads.ref(), float(rope_base), _ptr(pos_ids),
+                                           sec, _stream_ptr(stream)))
 
 
 def pevlm_block_prefill_workspace_bytes(layout: Layout, heads: Heads) -> int:

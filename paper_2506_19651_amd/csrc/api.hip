@@ -231,6 +231,25 @@ pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const 
     return PEVLM_OK;
 }
 
+pevlm_status pevlm_rope_mrope(void *q, void *k, int64_t num_tokens, const pevlm_heads *heads, double rope_base,
+                              const int32_t *pos_ids, const int32_t *section, void *stream)
+{
+    pevlm_status st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    if (!(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
+    if (num_tokens < 0 || num_tokens > 0x7fffffff) return fail(PEVLM_ERR_INVALID_ARG, "num_tokens out of range");
+    if ((q && !aligned16(q)) || (k && !aligned16(k))) return fail(PEVLM_ERR_INVALID_ARG, "q/k must be 16-byte aligned");
+    if (!section || section[0] < 0 || section[1] < 0 || section[2] < 0 ||
+        (int64_t)section[0] + section[1] + section[2] != heads->head_dim / 2)
+        return fail(PEVLM_ERR_INVALID_ARG, "section must hold three non-negative counts that add up to head_dim/2");
+    if (num_tokens == 0 || (!q && !k)) return PEVLM_OK;
+    if (!pos_ids || ((uintptr_t)pos_ids & 3)) return fail(PEVLM_ERR_INVALID_ARG, "pos_ids must be a 4-byte aligned device pointer");
+    hipError_t e = launch_rope_mrope(q, k, num_tokens, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
+                                     heads->dtype == PEVLM_BF16, rope_base, pos_ids, section[0], section[0] + section[1],
+                                     (hipStream_t)stream);
+    return e == hipSuccess ? PEVLM_OK : hip_fail(e, "mrope launch");
+}
+
 size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
 {
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;

@@ -159,6 +159,8 @@ hipError_t launch_build_query_items(const SeqTable &tab, int32_t tile_rows, int3
                                     int32_t item_offset, int32_t *qrow_of_compact, hipStream_t stream);
 hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
                        double rope_base, hipStream_t stream);
+hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
+                             const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);

@@ -13,21 +13,34 @@ struct RopeFreq {
 // (16 bytes each in bf16), forms the 8 angles once in fp64, reduces them to [-pi, pi], and then
 // walks over all query heads and key heads of that token.  D/16 lanes cover one token; a
 // wavefront covers 64/(D/16) tokens, so every load instruction touches whole 128-byte lines.
-template <int D, bool BF16>
+//
+// MROPE (three position axes: temporal, height, width; the scheme of the Qwen2.5-VL models of the
+// paper's experiments): the token's three ids come from pos3 [3][T] in device memory and pair index
+// i takes the id of the axis whose section holds i (sections are consecutive: [0, sec0),
+// [sec0, sec01), [sec01, D/2)); `tab` is not used.
+template <int D, bool BF16, bool MROPE>
 __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable tab, RopeFreq fr, int32_t Hq, int32_t Hkv,
-                                                   int32_t row_begin, int32_t row_end)
+                                                   int32_t row_begin, int32_t row_end, const int32_t *pos3, int64_t T,
+                                                   int32_t sec0, int32_t sec01)
 {
     constexpr int LANES_PER_TOKEN = D / 16;
     constexpr int TOKENS_PER_BLOCK = 256 / LANES_PER_TOKEN;
     int32_t tok = row_begin + blockIdx.x * TOKENS_PER_BLOCK + threadIdx.x / LANES_PER_TOKEN;
     if (tok >= row_end) return;
     int32_t i0 = (threadIdx.x % LANES_PER_TOKEN) * 8;
-    int32_t s = 0;
-    while (s + 1 < tab.num_seqs && tok >= tab.start[s + 1]) ++s;
-    double pos = (double)(tok - tab.start[s] + tab.pos_offset[s]);
+    double pos = 0.0, pos_axis[3] = {0.0, 0.0, 0.0};
+    if (MROPE) {
+#pragma unroll
+        for (int a = 0; a < 3; ++a) pos_axis[a] = (double)pos3[(int64_t)a * T + tok];
+    } else {
+        int32_t s = 0;
+        while (s + 1 < tab.num_seqs && tok >= tab.start[s + 1]) ++s;
+        pos = (double)(tok - tab.start[s] + tab.pos_offset[s]);
+    }
     float cs[8], sn[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+        if (MROPE) pos = i0 + j < sec0 ? pos_axis[0] : (i0 + j < sec01 ? pos_axis[1] : pos_axis[2]);
         double theta = pos * fr.inv_freq[i0 + j];
         const double two_pi = 6.283185307179586476925286766559;
         double r = theta - two_pi * rint(theta / two_pi);
@@ -91,22 +104,45 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
     }
 }
 
-hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
-                       double rope_base, hipStream_t stream)
+static void fill_freq(RopeFreq &fr, int32_t D, double rope_base)
+{
+    for (int i = 0; i < 64; ++i) fr.inv_freq[i] = i < D / 2 ? pow(rope_base, -2.0 * (double)i / (double)D) : 0.0;
+}
+
+template <bool MROPE>
+static hipError_t launch_rope_any(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
+                                  double rope_base, int32_t row_begin, int32_t row_end, const int32_t *pos3, int64_t T,
+                                  int32_t sec0, int32_t sec01, hipStream_t stream)
 {
     RopeFreq fr;
-    for (int i = 0; i < 64; ++i) fr.inv_freq[i] = i < D / 2 ? pow(rope_base, -2.0 * (double)i / (double)D) : 0.0;
-    int32_t n = tab.num_seqs;
-    int32_t row_begin = tab.start[0];
-    int32_t row_end = tab.start[n - 1] + tab.sink[n - 1] + tab.ctx[n - 1] + tab.query[n - 1];
+    fill_freq(fr, D, rope_base);
     if (row_end <= row_begin) return hipSuccess;
     int32_t tokens_per_block = 256 / (D / 16);
     dim3 grid((row_end - row_begin + tokens_per_block - 1) / tokens_per_block);
-    if (D == 128 && bf16) hipLaunchKernelGGL((rope_kernel<128, true>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end);
-    else if (D == 128) hipLaunchKernelGGL((rope_kernel<128, false>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end);
-    else if (bf16) hipLaunchKernelGGL((rope_kernel<64, true>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end);
-    else hipLaunchKernelGGL((rope_kernel<64, false>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end);
+#define PEVLM_ROPE_LAUNCH(DD, BB) \
+    hipLaunchKernelGGL((rope_kernel<DD, BB, MROPE>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end, pos3, T, sec0, sec01)
+    if (D == 128 && bf16) PEVLM_ROPE_LAUNCH(128, true);
+    else if (D == 128) PEVLM_ROPE_LAUNCH(128, false);
+    else if (bf16) PEVLM_ROPE_LAUNCH(64, true);
+    else PEVLM_ROPE_LAUNCH(64, false);
+#undef PEVLM_ROPE_LAUNCH
     return hipGetLastError();
+}
+
+hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
+                       double rope_base, hipStream_t stream)
+{
+    int32_t n = tab.num_seqs;
+    int32_t row_begin = tab.start[0];
+    int32_t row_end = tab.start[n - 1] + tab.sink[n - 1] + tab.ctx[n - 1] + tab.query[n - 1];
+    return launch_rope_any<false>(q, k, tab, Hq, Hkv, D, bf16, rope_base, row_begin, row_end, nullptr, 0, 0, 0, stream);
+}
+
+hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
+                             const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream)
+{
+    SeqTable tab = {};
+    return launch_rope_any<true>(q, k, tab, Hq, Hkv, D, bf16, rope_base, 0, (int32_t)T, pos3, T, sec0, sec01, stream);
 }
 
 }  // namespace pevlm

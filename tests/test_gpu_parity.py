@@ -233,3 +233,77 @@ def test_roofline_probes_run_and_copy_is_exact():
         P.pevlm_probe_copy(dst, src, 24)
     with pytest.raises(P.PevlmError):
         P.pevlm_probe_mfma_bf16(scratch, 0, 10)
+
+
+# ------------------------------------------------------------------------------------ multimodal RoPE
+MROPE_CASES = [
+    # name, dtype, Hq, Hkv, D, seqs, frame_tokens, grid_w, section
+    ("f32_d64", "f32", 4, 2, 64, [(40, 32, 96, 9), (3, 16, 40, 5)], 16, 4, (8, 12, 12)),
+    ("bf16_d128_qwen_split", "bf16", 8, 2, 128, [(300, 512, 1536, 70)], 256, 16, (16, 24, 24)),
+    ("bf16_d128_ragged_sections", "bf16", 4, 1, 128, [(100, 196, 700, 33)], 196, 14, (5, 20, 39)),
+    ("bf16_d64_one_axis_empty", "bf16", 4, 4, 64, [(64, 64, 320, 8)], 64, 8, (12, 20, 0)),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs,ft,gw,section", MROPE_CASES, ids=[c[0] for c in MROPE_CASES])
+def test_mrope_against_oracle(oracle, name, dtype, Hq, Hkv, D, seqs, ft, gw, section):
+    """pevlm_rope_mrope element by element against the oracle's three-axis rotation, and the whole
+    path (three-axis RoPE -> block prefill -> question attention) against the oracle's attention
+    over its own rotated tensors."""
+    w = W.Workload(name, 13, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
+    data = W.generate(w)
+    ids = W.mrope_position_ids(w, ft, gw)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    ids_d = torch.from_numpy(ids).to(DEV)
+    P.pevlm_rope_mrope(q, k, w.total_tokens, heads, w.rope_base, ids_d, section)
+    out = torch.full_like(q, float("nan"))
+    P.pevlm_block_prefill_attn(q, k, v, out, lay, heads)
+    P.pevlm_query_attn(q, k, v, out, lay, heads)
+    torch.cuda.synchronize()
+    q_exact = oracle.rope_mrope(data["q"], ids, section, w.rope_base)
+    k_exact = oracle.rope_mrope(data["k"], ids, section, w.rope_base)
+    for got, exact in ((to_host_f32(q), q_exact), (to_host_f32(k), k_exact)):
+        err = np.abs(got - exact)
+        if dtype == "bf16":
+            assert np.all(err <= np.abs(exact) * 2.0 ** -8 + 1e-6)  # one rounding of the exact rotation
+        else:
+            assert err.max() <= 2e-6
+    want, _ = oracle.attn(q_exact, k_exact, data["v"], oracle_layout(oracle, w))
+    got = to_host_f32(out)
+    if dtype == "bf16":
+        check_bf16(got, want, name)
+    else:
+        assert np.max(np.abs(got - want)) <= F32_TOL
+
+
+def test_mrope_with_equal_axes_is_sequential_rope_bitwise():
+    w = W.small_variant(W.CONFIGS["c2"], "mrope_eq", [(256, 512, 1024, 64), (0, 128, 300, 7)])
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q1, k1 = to_device(data["q"]), to_device(data["k"])
+    q2, k2 = q1.clone(), k1.clone()
+    offs = [11, 4000]
+    P.pevlm_rope_seq(q1, k1, lay, heads, w.rope_base, offs)
+    pos = np.concatenate([np.arange(S + C + Q, dtype=np.int32) + o for (S, _b, C, Q), o in zip(w.seqs, offs)])
+    ids = torch.from_numpy(np.stack([pos, pos, pos])).to(DEV)
+    P.pevlm_rope_mrope(q2, k2, w.total_tokens, heads, w.rope_base, ids, (16, 24, 24))
+    torch.cuda.synchronize()
+    assert torch.equal(q1.view(torch.int16), q2.view(torch.int16)) and torch.equal(k1.view(torch.int16), k2.view(torch.int16))
+
+
+def test_mrope_full_size_c3_sampled_rows(oracle):
+    """The 64K-token workload with the ids of a 16x16-token-per-frame video prompt."""
+    w = W.CONFIGS["c3"]
+    data = W.generate(w)
+    ids = W.mrope_position_ids(w, 256, 16)
+    _lay, heads = layout_heads(w)
+    q, k = to_device(data["q"]), to_device(data["k"])
+    P.pevlm_rope_mrope(q, k, w.total_tokens, heads, w.rope_base, torch.from_numpy(ids).to(DEV), (16, 24, 24))
+    torch.cuda.synchronize()
+    rows = W.sample_rows(w, n_random=256, max_question_rows=16)
+    idx = torch.from_numpy(rows).to(DEV)
+    for t, key in ((q, "q"), (k, "k")):
+        exact = oracle.rope_mrope(data[key], ids, (16, 24, 24), w.rope_base, rows=rows)
+        err = np.abs(to_host_f32(t[idx]) - exact)
+        assert np.all(err <= np.abs(exact) * 2.0 ** -8 + 1e-6)

@@ -149,6 +149,15 @@ def test_argument_validation_without_gpu():
     assert q(-1) == P.binding.PEVLM_ERR_INVALID_ARG and q(65) == P.binding.PEVLM_ERR_INVALID_ARG
     assert q(0) == P.binding.PEVLM_ERR_WORKSPACE_TOO_SMALL
     assert lib.pevlm_rope_seq(fake, fake, lay.ref(), heads.ref(), -1.0, None, None) == P.binding.PEVLM_ERR_INVALID_ARG
+    sec = lambda *v: (ctypes.c_int32 * 3)(*v)
+    mr = lambda n, section, ids=fake, base=1e4: lib.pevlm_rope_mrope(fake, fake, n, heads.ref(), base, ids, section, None)
+    assert mr(10, sec(8, 12, 11)) == P.binding.PEVLM_ERR_INVALID_ARG and "section" in P.pevlm_last_error()
+    assert mr(10, sec(-1, 21, 12)) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert mr(10, None) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert mr(10, sec(8, 12, 12), None) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert mr(-1, sec(8, 12, 12)) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert mr(10, sec(8, 12, 12), fake, 0.0) == P.binding.PEVLM_ERR_INVALID_ARG
+    assert mr(0, sec(8, 12, 12)) == P.binding.PEVLM_OK  # nothing to do, nothing launched
     assert P.pevlm_block_prefill_workspace_bytes(bad_sum, heads) == 0
     assert P.pevlm_query_workspace_bytes(lay, heads, 0) > 0
 
