@@ -151,6 +151,47 @@ def main():
         "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
     }
 
+    # the same step with RoPE folded into the attention calls (the prefill call rotates K in place and
+    # fills the cos/sin table; q0 stays un-rotated); outputs are bit-identical to the three-call path
+    ws_pf = torch.empty(P.pevlm_block_prefill_rope_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
+    ws_qf = torch.empty(P.pevlm_query_rope_workspace_bytes(lay, heads, args.num_splits), dtype=torch.uint8, device=dev)
+    out_f = torch.zeros_like(q0)
+
+    def step_fused(ev=None):
+        if ev:
+            ev[0].record(stream)
+        if ev:
+            ev[1].record(stream)
+        P.pevlm_block_prefill_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, workspace=ws_pf, stream=stream)
+        if ev:
+            ev[2].record(stream)
+        P.pevlm_query_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, num_splits=args.num_splits, workspace=ws_qf,
+                                stream=stream)
+        if ev:
+            ev[3].record(stream)
+
+    k.copy_(k0)
+    step_fused()
+    torch.cuda.synchronize()
+    fused_matches = bool(torch.equal(out_f.view(torch.int16), first_out.view(torch.int16)))
+    for _ in range(args.warmup):
+        step_fused()
+    events_f = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    tf0 = time.perf_counter()
+    for i in range(args.steps):
+        step_fused(events_f[i])
+    torch.cuda.synchronize()
+    tf1 = time.perf_counter()
+    ms_step_f = (tf1 - tf0) * 1e3 / args.steps
+    result["fused_rope"] = {
+        "ms_per_step": round(ms_step_f, 4),
+        "value": round((f_prefill + f_query) / (ms_step_f * 1e-3) / 1e12, 3),
+        "ms_block_prefill_incl_k_rope": round(float(np.mean([e[1].elapsed_time(e[2]) for e in events_f])), 4),
+        "ms_query_attn": round(float(np.mean([e[2].elapsed_time(e[3]) for e in events_f])), 4),
+        "bit_identical_to_three_call_path": fused_matches,
+    }
+
     if not args.no_probes:
         # what the device sustains: bf16 MFMA issue (two workgroups per CU, as the attention kernel
         # runs) and a 1 GiB streaming copy; the copy is also the known-size kernel that scales the

@@ -128,6 +128,33 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
                               const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The two attention calls with the sequential RoPE step (Sec. "Position Encoding") folded in, so
+ * that q is never read and re-written by a separate pass.  `q` holds UN-rotated queries and is not
+ * modified: each workgroup rotates its query rows once, on the fly, at
+ * pos = t - cu_seqlens[s] + pos_offset[s] (pos_offset: HOST [num_seqs] or NULL = 0) with the same
+ * arithmetic and the same single rounding to bf16 as pevlm_rope_seq, so `out` and `lse` are bit for
+ * bit those of the three-call path.  Keys:
+ *   pevlm_block_prefill_attn_rope, k_is_rotated == 0: k holds un-rotated keys of ALL tokens of the
+ *       layout and is rotated IN PLACE first (as pevlm_rope_seq(NULL, k, ...) would), by the kernel
+ *       that also fills the (cos, sin) table the query rotation reads;
+ *   k_is_rotated != 0: k is already rotated and only read.
+ *   pevlm_query_attn_rope: k must already be rotated (by either of the above).
+ * bf16 tensors only (PEVLM_ERR_UNSUPPORTED otherwise).  The workspace additionally holds the
+ * (cos, sin) table: head_dim * 4 bytes per token (prefill) or per question row (question call).
+ * Everything else is as for pevlm_block_prefill_attn / pevlm_query_attn.
+ */
+size_t pevlm_block_prefill_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads);
+pevlm_status pevlm_block_prefill_attn_rope(const void *q, void *k, const void *v, void *out, float *lse,
+                                           const pevlm_layout *layout, const pevlm_heads *heads, double rope_base,
+                                           const int32_t *pos_offset, int32_t k_is_rotated, void *workspace,
+                                           size_t workspace_bytes, void *stream);
+size_t pevlm_query_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits);
+pevlm_status pevlm_query_attn_rope(const void *q, const void *k, const void *v, void *out, float *lse,
+                                   const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                                   double rope_base, const int32_t *pos_offset, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
 /* Message of the last failure on the calling thread (static storage, never NULL). */
 const char *pevlm_last_error(void);
 /* Library version: major * 10000 + minor * 100 + patch. */

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     pevlm_block_prefill_attn,
+    pevlm_block_prefill_attn_rope,
+    pevlm_block_prefill_rope_workspace_bytes,
     pevlm_block_prefill_workspace_bytes,
     pevlm_last_error,
     pevlm_prefill_tile_rows,
@@ -19,6 +21,8 @@ from .binding import (  # noqa: F401
     pevlm_probe_copy,
     pevlm_probe_mfma_bf16,
     pevlm_query_attn,
+    pevlm_query_attn_rope,
+    pevlm_query_rope_workspace_bytes,
     pevlm_query_tile_rows,
     pevlm_query_workspace_bytes,
     pevlm_query_worklist_host,

@@ -68,6 +68,14 @@ def load_library():
         lib.pevlm_query_workspace_bytes.argtypes = [LP, HP, i32]
         lib.pevlm_query_attn.restype = ctypes.c_int
         lib.pevlm_query_attn.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, vp, ctypes.c_size_t, vp]
+        lib.pevlm_block_prefill_rope_workspace_bytes.restype = ctypes.c_size_t
+        lib.pevlm_block_prefill_rope_workspace_bytes.argtypes = [LP, HP]
+        lib.pevlm_block_prefill_attn_rope.restype = ctypes.c_int
+        lib.pevlm_block_prefill_attn_rope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, ctypes.c_double, vp, i32, vp, ctypes.c_size_t, vp]
+        lib.pevlm_query_rope_workspace_bytes.restype = ctypes.c_size_t
+        lib.pevlm_query_rope_workspace_bytes.argtypes = [LP, HP, i32]
+        lib.pevlm_query_attn_rope.restype = ctypes.c_int
+        lib.pevlm_query_attn_rope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, ctypes.c_double, vp, vp, ctypes.c_size_t, vp]
         lib.pevlm_last_error.restype = ctypes.c_char_p
         lib.pevlm_version.restype = i32
         lib.pevlm_prefill_tile_rows.restype = i32
@@ -192,6 +200,39 @@ def pevlm_rope_seq(q, k, layout: Layout, heads: Heads, rope_base: float, pos_off
     offp = None if off is None else off.ctypes.data_as(ctypes.c_void_p)
     _check(load_library().pevlm_rope_seq(_ptr(q), _ptr(k), layout.ref(), heads.ref(), float(rope_base), offp,
                                          _stream_ptr(stream)))
+
+
+def _offsets(pos_offset):
+    off = None if pos_offset is None else np.ascontiguousarray(pos_offset, dtype=np.int32)
+    return off, (None if off is None else off.ctypes.data_as(ctypes.c_void_p))
+
+
+def pevlm_block_prefill_rope_workspace_bytes(layout: Layout, heads: Heads) -> int:
+    return int(load_library().pevlm_block_prefill_rope_workspace_bytes(layout.ref(), heads.ref()))
+
+
+def pevlm_block_prefill_attn_rope(q, k, v, out, layout: Layout, heads: Heads, rope_base: float, pos_offset=None,
+                                  k_is_rotated: bool = False, lse=None, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_block_prefill_rope_workspace_bytes(layout, heads), q)
+    _off, offp = _offsets(pos_offset)
+    _check(load_library().pevlm_block_prefill_attn_rope(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
+                                                        heads.ref(), float(rope_base), offp, int(bool(k_is_rotated)),
+                                                        _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
+
+
+def pevlm_query_rope_workspace_bytes(layout: Layout, heads: Heads, num_splits: int = 0) -> int:
+    return int(load_library().pevlm_query_rope_workspace_bytes(layout.ref(), heads.ref(), int(num_splits)))
+
+
+def pevlm_query_attn_rope(q, k, v, out, layout: Layout, heads: Heads, rope_base: float, pos_offset=None, num_splits: int = 0,
+                          lse=None, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_query_rope_workspace_bytes(layout, heads, num_splits), q)
+    _off, offp = _offsets(pos_offset)
+    _check(load_library().pevlm_query_attn_rope(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(), heads.ref(),
+                                                int(num_splits), float(rope_base), offp, _ptr(workspace),
+                                                workspace.numel(), _stream_ptr(stream)))
 
 
 def pevlm_rope_mrope(q, k, num_tokens: int, heads: Heads, rope_base: float, pos_ids, section, stream=None):

@@ -174,13 +174,16 @@ static int32_t auto_splits(const pevlm_layout *lay, const pevlm_heads *h)
     return (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, cap), PEVLM_MAX_SPLITS));
 }
 
+// bytes of the (cos, sin) table of the fused query rotation: head_dim/2 pairs of floats per entry
+static size_t rope_table_bytes(int64_t entries, const pevlm_heads *h) { return align256((size_t)entries * h->head_dim * sizeof(float)); }
+
 struct QueryPlan {
     int32_t num_splits, tile_rows;
     int64_t n_items, total_q;
-    size_t off_items, off_qrow, off_ml, off_acc, bytes;
+    size_t off_items, off_qrow, off_ml, off_acc, off_rope, bytes;
 };
 
-static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits)
+static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits, bool fuse_rope = false)
 {
     QueryPlan p;
     p.tile_rows = tile_rows_of(h, true);
@@ -196,6 +199,8 @@ static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32
     off += align256((size_t)p.num_splits * p.total_q * h->n_q_heads * 2 * sizeof(float));
     p.off_acc = off;
     off += align256((size_t)p.num_splits * p.total_q * h->n_q_heads * h->head_dim * sizeof(float));
+    p.off_rope = off;
+    if (fuse_rope) off += rope_table_bytes(p.total_q, h);  // one entry per compact question row
     p.bytes = off;
     return p;
 }
@@ -225,7 +230,7 @@ pevlm_status pevlm_rope_seq(void *q, void *k, const pevlm_layout *layout, const 
         SeqTable tab;
         fill_table(layout, s0, std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0), pos_offset, &tab);
         hipError_t e = launch_rope(q, k, tab, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
-                                   heads->dtype == PEVLM_BF16, rope_base, (hipStream_t)stream);
+                                   heads->dtype == PEVLM_BF16, rope_base, nullptr, (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "rope launch");
     }
     return PEVLM_OK;
@@ -250,15 +255,28 @@ pevlm_status pevlm_rope_mrope(void *q, void *k, int64_t num_tokens, const pevlm_
     return e == hipSuccess ? PEVLM_OK : hip_fail(e, "mrope launch");
 }
 
-size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
+static size_t prefill_workspace(const pevlm_layout *layout, const pevlm_heads *heads, bool fuse_rope)
 {
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
-    return align256((size_t)count_prefill_items(layout, tile_rows_of(heads, false)) * sizeof(pevlm_work_item)) + 256;
+    size_t n = align256((size_t)count_prefill_items(layout, tile_rows_of(heads, false)) * sizeof(pevlm_work_item));
+    if (fuse_rope) n += rope_table_bytes(layout->cu_seqlens[layout->num_seqs], heads);
+    return n + 256;
 }
 
-pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *v, void *out, float *lse,
-                                      const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
-                                      size_t workspace_bytes, void *stream)
+size_t pevlm_block_prefill_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
+{
+    return prefill_workspace(layout, heads, false);
+}
+
+size_t pevlm_block_prefill_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
+{
+    return prefill_workspace(layout, heads, true);
+}
+
+static pevlm_status prefill_impl(const void *q, const void *k, const void *v, void *out, float *lse,
+                                 const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
+                                 size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
+                                 const int32_t *pos_offset, bool rotate_k)
 {
     pevlm_status st = check_layout(layout);
     if (st != PEVLM_OK) return st;
@@ -269,30 +287,47 @@ pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *
     if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
         return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (fuse_rope && heads->dtype != PEVLM_BF16)
+        return fail(PEVLM_ERR_UNSUPPORTED, "the fused query rotation exists for bf16 tensors only");
+    if (fuse_rope && !(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
     int32_t tile_rows = tile_rows_of(heads, false);
     int64_t n_items = count_prefill_items(layout, tile_rows);
-    if (n_items == 0) return PEVLM_OK;
+    if (n_items == 0) {  // no sink or context rows: nothing to attend, but the keys are still rotated if asked
+        if (fuse_rope && rotate_k && layout->cu_seqlens[layout->num_seqs] > 0)
+            return pevlm_rope_seq(nullptr, const_cast<void *>(k), layout, heads, rope_base, pos_offset, stream);
+        return PEVLM_OK;
+    }
     if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
-    size_t need = pevlm_block_prefill_workspace_bytes(layout, heads);
+    size_t need = prefill_workspace(layout, heads, fuse_rope);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
         return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "prefill workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
                     workspace ? workspace_bytes : (size_t)0);
     hipStream_t hs = (hipStream_t)stream;
     pevlm_work_item *items = (pevlm_work_item *)workspace;
+    float *rope_tab = (float *)((char *)workspace + align256((size_t)n_items * sizeof(pevlm_work_item)));
     int32_t offset = 0;
     for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
         SeqTable tab;
         int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
-        fill_table(layout, s0, n, nullptr, &tab);
+        fill_table(layout, s0, n, pos_offset, &tab);
         for (int32_t i = 0; i < n; ++i)
             tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], tile_rows);
         if (tab.item_base[n] > 0) {
             hipError_t e = launch_build_prefill_items(tab, tile_rows, items, offset, hs);
             if (e != hipSuccess) return hip_fail(e, "work-list builder launch");
         }
+        if (fuse_rope) {  // table entries = packed rows of this chunk's sequences
+            hipError_t e = rotate_k ? launch_rope(nullptr, const_cast<void *>(k), tab, heads->n_q_heads, heads->n_kv_heads,
+                                                  heads->head_dim, true, rope_base, rope_tab, hs)
+                                    : launch_rope_table(rope_tab, nullptr, tab, heads->head_dim, rope_base,
+                                                        layout->cu_seqlens[s0], layout->cu_seqlens[s0 + n], hs);
+            if (e != hipSuccess) return hip_fail(e, "rope table launch");
+        }
         offset += tab.item_base[n];
     }
     p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
+    p.rope_tab = fuse_rope ? rope_tab : nullptr;
+    p.rope_compact_rows = 0;
     p.items = items;
     p.n_items = (int32_t)n_items;
     p.n_q_heads = heads->n_q_heads;
@@ -304,6 +339,22 @@ pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *
     return PEVLM_OK;
 }
 
+pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                                      const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    return prefill_impl(q, k, v, out, lse, layout, heads, workspace, workspace_bytes, stream, false, 0.0, nullptr, false);
+}
+
+pevlm_status pevlm_block_prefill_attn_rope(const void *q, void *k, const void *v, void *out, float *lse,
+                                           const pevlm_layout *layout, const pevlm_heads *heads, double rope_base,
+                                           const int32_t *pos_offset, int32_t k_is_rotated, void *workspace,
+                                           size_t workspace_bytes, void *stream)
+{
+    return prefill_impl(q, k, v, out, lse, layout, heads, workspace, workspace_bytes, stream, true, rope_base, pos_offset,
+                        k_is_rotated == 0);
+}
+
 size_t pevlm_query_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)
 {
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
@@ -311,9 +362,17 @@ size_t pevlm_query_workspace_bytes(const pevlm_layout *layout, const pevlm_heads
     return plan_query(layout, heads, num_splits).bytes + 256;
 }
 
-pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void *out, float *lse,
-                              const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
-                              void *workspace, size_t workspace_bytes, void *stream)
+size_t pevlm_query_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)
+{
+    if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
+    if (num_splits < 0 || num_splits > PEVLM_MAX_SPLITS) return 0;
+    return plan_query(layout, heads, num_splits, true).bytes + 256;
+}
+
+static pevlm_status query_impl(const void *q, const void *k, const void *v, void *out, float *lse,
+                               const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                               void *workspace, size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
+                               const int32_t *pos_offset)
 {
     pevlm_status st = check_layout(layout);
     if (st != PEVLM_OK) return st;
@@ -326,7 +385,10 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
     if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
         return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    QueryPlan plan = plan_query(layout, heads, num_splits);
+    if (fuse_rope && heads->dtype != PEVLM_BF16)
+        return fail(PEVLM_ERR_UNSUPPORTED, "the fused query rotation exists for bf16 tensors only");
+    if (fuse_rope && !(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
+    QueryPlan plan = plan_query(layout, heads, num_splits, fuse_rope);
     if (plan.total_q == 0) return PEVLM_OK;
     if (plan.n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
     if (!workspace || workspace_bytes < plan.bytes || ((uintptr_t)workspace & 255))
@@ -338,11 +400,13 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
     int32_t *qrow = (int32_t *)(ws + plan.off_qrow);
     float *ml = (float *)(ws + plan.off_ml);
     float *acc = (float *)(ws + plan.off_acc);
+    float *rope_tab = (float *)(ws + plan.off_rope);
     int32_t item_offset = 0, qrow_base = 0;
     for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
         SeqTable tab;
         int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
-        fill_table(layout, s0, n, nullptr, &tab);
+        fill_table(layout, s0, n, pos_offset, &tab);
+        const int32_t entry_begin = qrow_base;
         for (int32_t i = 0; i < n; ++i) {
             tab.item_base[i + 1] = tab.item_base[i] + query_tiles_of_seq(tab.query[i], plan.tile_rows) * plan.num_splits;
             tab.qrow_base[i] = qrow_base;
@@ -352,10 +416,16 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
             hipError_t e = launch_build_query_items(tab, plan.tile_rows, plan.num_splits, (int32_t)plan.total_q,
                                                     kKeyTile, items, item_offset, qrow, hs);
             if (e != hipSuccess) return hip_fail(e, "query work-list builder launch");
+            if (fuse_rope) {  // table entries = compact question rows of this chunk (mapped through qrow)
+                e = launch_rope_table(rope_tab, qrow, tab, heads->head_dim, rope_base, entry_begin, qrow_base, hs);
+                if (e != hipSuccess) return hip_fail(e, "rope table launch");
+            }
         }
         item_offset += tab.item_base[n];
     }
     p.q = q; p.k = k; p.v = v;
+    p.rope_tab = fuse_rope ? rope_tab : nullptr;
+    p.rope_compact_rows = fuse_rope ? (int32_t)plan.total_q : 0;
     p.part_acc = acc;
     p.part_ml = ml;
     p.items = items;
@@ -377,6 +447,21 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
     e = launch_merge(m, hs);
     if (e != hipSuccess) return hip_fail(e, "merge launch");
     return PEVLM_OK;
+}
+
+pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                              const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, false, 0.0, nullptr);
+}
+
+pevlm_status pevlm_query_attn_rope(const void *q, const void *k, const void *v, void *out, float *lse,
+                                   const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits, double rope_base,
+                                   const int32_t *pos_offset, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, true, rope_base,
+                      pos_offset);
 }
 
 int64_t pevlm_prefill_worklist_host(const pevlm_layout *layout, int32_t tile_rows, pevlm_work_item *items,

@@ -18,6 +18,7 @@
 // matrix cores and the vector ALU of a SIMD overlap within one instruction stream as well as
 // across the two resident wavefronts.
 #include "bf16_device.h"
+#include "rope_math.h"
 
 namespace pevlm {
 
@@ -235,7 +236,9 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
     }
 }
 
-template <int D, bool PARTIAL>
+// ROPEQ: q holds un-rotated queries; each wavefront rotates its 32 rows once, right after loading
+// them, from the (cos, sin) table of the call (the sequential positions of Sec. "Position Encoding").
+template <int D, bool PARTIAL, bool ROPEQ>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads)
 {
     using C = TileCfg<D>;
@@ -294,6 +297,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     const int32_t wr_lo = it.q_start + rg * 32;
     const int32_t wr_hi = it.q_start + ((rg * 32 + 31 < it.q_rows) ? rg * 32 + 31 : it.q_rows - 1);
 
+    // (cos, sin) of this lane's row for the fused query rotation: fetched first, so that the loads
+    // are in flight together with the Q rows
+    f32x4 rope_cs[ROPEQ ? KSTEPS / 2 : 1][4];
+    if (ROPEQ) {
+        int64_t entry = my_row;
+        if (p.rope_compact_rows > 0)
+            entry = it.reserved % p.rope_compact_rows + (row_in_tile < it.q_rows ? row_in_tile : it.q_rows - 1);
+        const f32x4 *tab = reinterpret_cast<const f32x4 *>(p.rope_tab + entry * D) + g32 * 4;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS / 2; ++kk)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rope_cs[kk][j] = tab[kk * 8 + j];
+    }
     const uint32_t lds_k_addr = (uint32_t)(size_t)LDS_PTR(void, lds_k);
     const uint32_t lds_v_addr = (uint32_t)(size_t)LDS_PTR(void, lds_v);
     // Q rows of the wave are fetched with whole-row (coalesced) direct-to-LDS loads into a
@@ -419,6 +435,28 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk)
         qf[kk] = *reinterpret_cast<const bf16x8 *>(wave_slice + l32 * ROWB + (((kk * 2 + g32) ^ (l32 & (CH - 1))) << 4));
+    if (ROPEQ) {
+        // this lane holds dims kk*16 + g32*8 + e of its row: pair index i < D/2 in qf[kk], its partner
+        // i + D/2 in qf[kk + KSTEPS/2]
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS / 2; ++kk) {
+            const f32x4 *cs = rope_cs[kk];
+            const u32x4 lo = __builtin_bit_cast(u32x4, qf[kk]), hi = __builtin_bit_cast(u32x4, qf[kk + KSTEPS / 2]);
+            u32x4 rl, rh;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float a0 = __uint_as_float(lo[w] << 16), a1 = __uint_as_float(lo[w] & 0xffff0000u);
+                const float b0 = __uint_as_float(hi[w] << 16), b1 = __uint_as_float(hi[w] & 0xffff0000u);
+                float r0, r1, t0, t1;
+                rope_rotate(a0, b0, cs[w][0], cs[w][1], r0, t0);
+                rope_rotate(a1, b1, cs[w][2], cs[w][3], r1, t1);
+                rl[w] = rope_pack_bf16(r0, r1);
+                rh[w] = rope_pack_bf16(t0, t1);
+            }
+            qf[kk] = __builtin_bit_cast(bf16x8, rl);
+            qf[kk + KSTEPS / 2] = __builtin_bit_cast(bf16x8, rh);
+        }
+    }
 
     // m_ref: reference maximum of this lane's row in base-2 units, c_log2 * score (-inf: none yet)
     float m_ref = -INFINITY, l_run = 0.f;
@@ -589,13 +627,17 @@ hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStr
     int32_t pack = (uniform && G > 1) ? 1 : 0;  // short items are taken for several heads of a KV group at once
     int32_t n_logical = p.n_items * p.n_q_heads;
     dim3 grid((n_logical + 7) / 8 * 8), block(256);
+#define PEVLM_ATTN_LAUNCH(DD, PP, RR) \
+    hipLaunchKernelGGL((attn_bf16_kernel<DD, PP, RR>), grid, block, 0, stream, p, n_logical, heads_inner, pack)
+    const bool rope = p.rope_tab != nullptr;
     if (D == 128) {
-        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
-        else hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
+        if (partial) { if (rope) PEVLM_ATTN_LAUNCH(128, true, true); else PEVLM_ATTN_LAUNCH(128, true, false); }
+        else { if (rope) PEVLM_ATTN_LAUNCH(128, false, true); else PEVLM_ATTN_LAUNCH(128, false, false); }
     } else {
-        if (partial) hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
-        else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, 0, stream, p, n_logical, heads_inner, pack);
+        if (partial) { if (rope) PEVLM_ATTN_LAUNCH(64, true, true); else PEVLM_ATTN_LAUNCH(64, true, false); }
+        else { if (rope) PEVLM_ATTN_LAUNCH(64, false, true); else PEVLM_ATTN_LAUNCH(64, false, false); }
     }
+#undef PEVLM_ATTN_LAUNCH
     return hipGetLastError();
 }
 

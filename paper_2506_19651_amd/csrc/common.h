@@ -136,6 +136,11 @@ struct AttnParams {
     int32_t n_items;
     int32_t n_q_heads, n_kv_heads;
     float scale;                    // softmax scale
+    // fused query rotation (bf16 kernels): q holds un-rotated queries and rope_tab (cos, sin) pairs
+    // [entries][head_dim/2]; the entry of a row is its packed row (rope_compact_rows == 0) or its
+    // compact question row (item.reserved % rope_compact_rows + row in tile).  NULL: q is rotated.
+    const float *rope_tab;
+    int32_t rope_compact_rows;
     HeadTable heads;
 };
 
@@ -157,12 +162,15 @@ hipError_t launch_build_prefill_items(const SeqTable &tab, int32_t tile_rows, pe
 hipError_t launch_build_query_items(const SeqTable &tab, int32_t tile_rows, int32_t num_splits,
                                     int32_t total_q_rows, int32_t align, pevlm_work_item *items,
                                     int32_t item_offset, int32_t *qrow_of_compact, hipStream_t stream);
+// table != NULL (bf16 only): also stores (cos, sin) [packed row][D/2] for the fused query rotation
 hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
-                       double rope_base, hipStream_t stream);
+                       double rope_base, float *table, hipStream_t stream);
+hipError_t launch_rope_table(float *table, const int32_t *row_of_entry, const SeqTable &tab, int32_t D, double rope_base,
+                             int32_t entry_begin, int32_t entry_end, hipStream_t stream);
 hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
                              const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
-hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);  // p.rope_tab selects the fused variant
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);
 hipError_t launch_probe_mfma(float *sink, int32_t workgroups, int32_t iters, hipStream_t stream);
 hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t stream);

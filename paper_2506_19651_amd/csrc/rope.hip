@@ -2,12 +2,9 @@
 // rotated at its index in the whole sequence; nothing restarts at a block boundary.
 // HBM-bound: each element of q and k is read once and written once.
 #include "common.h"
+#include "rope_math.h"
 
 namespace pevlm {
-
-struct RopeFreq {
-    double inv_freq[64];  // rope_base^(-2i/D), i < D/2
-};
 
 // A lane owns 8 consecutive pair indices i of one token: it loads x[i..i+8) and x[i+D/2..i+D/2+8)
 // (16 bytes each in bf16), forms the 8 angles once in fp64, reduces them to [-pi, pi], and then
@@ -21,7 +18,7 @@ struct RopeFreq {
 template <int D, bool BF16, bool MROPE>
 __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable tab, RopeFreq fr, int32_t Hq, int32_t Hkv,
                                                    int32_t row_begin, int32_t row_end, const int32_t *pos3, int64_t T,
-                                                   int32_t sec0, int32_t sec01)
+                                                   int32_t sec0, int32_t sec01, float2 *table)
 {
     constexpr int LANES_PER_TOKEN = D / 16;
     constexpr int TOKENS_PER_BLOCK = 256 / LANES_PER_TOKEN;
@@ -41,17 +38,12 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         if (MROPE) pos = i0 + j < sec0 ? pos_axis[0] : (i0 + j < sec01 ? pos_axis[1] : pos_axis[2]);
-        double theta = pos * fr.inv_freq[i0 + j];
-        const double two_pi = 6.283185307179586476925286766559;
-        double r = theta - two_pi * rint(theta / two_pi);
-        if (BF16) {
-            sincosf((float)r, &sn[j], &cs[j]);
-        } else {
-            double sd, cd;
-            sincos(r, &sd, &cd);
-            sn[j] = (float)sd;
-            cs[j] = (float)cd;
-        }
+        rope_cos_sin<!BF16>(pos, fr.inv_freq[i0 + j], cs[j], sn[j]);
+    }
+    if (table) {  // by-product for the fused query rotation of the attention kernels: entry = packed row
+        float2 *dst = table + (int64_t)tok * (D / 2) + i0;
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) *reinterpret_cast<float4 *>(dst + j) = make_float4(cs[j], sn[j], cs[j + 1], sn[j + 1]);
     }
     for (int pass = 0; pass < 2; ++pass) {
         void *base = pass == 0 ? q : k;
@@ -69,14 +61,11 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
                 for (int w = 0; w < 4; ++w) {
                     float a0 = __uint_as_float(l[w] << 16), a1 = __uint_as_float(l[w] & 0xffff0000u);
                     float b0 = __uint_as_float(u[w] << 16), b1 = __uint_as_float(u[w] & 0xffff0000u);
-                    float r0 = a0 * cs[2 * w] - b0 * sn[2 * w], r1 = a1 * cs[2 * w + 1] - b1 * sn[2 * w + 1];
-                    float t0 = b0 * cs[2 * w] + a0 * sn[2 * w], t1 = b1 * cs[2 * w + 1] + a1 * sn[2 * w + 1];
-                    uint32_t x0 = __float_as_uint(r0), x1 = __float_as_uint(r1);
-                    uint32_t y0 = __float_as_uint(t0), y1 = __float_as_uint(t1);
-                    x0 += 0x7fffu + ((x0 >> 16) & 1u); x1 += 0x7fffu + ((x1 >> 16) & 1u);
-                    y0 += 0x7fffu + ((y0 >> 16) & 1u); y1 += 0x7fffu + ((y1 >> 16) & 1u);
-                    ol[w] = (x0 >> 16) | (x1 & 0xffff0000u);
-                    ou[w] = (y0 >> 16) | (y1 & 0xffff0000u);
+                    float r0, r1, t0, t1;
+                    rope_rotate(a0, b0, cs[2 * w], sn[2 * w], r0, t0);
+                    rope_rotate(a1, b1, cs[2 * w + 1], sn[2 * w + 1], r1, t1);
+                    ol[w] = rope_pack_bf16(r0, r1);
+                    ou[w] = rope_pack_bf16(t0, t1);
                 }
                 *reinterpret_cast<uint4 *>(x) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
                 *reinterpret_cast<uint4 *>(x + D / 2) = make_uint4(ou[0], ou[1], ou[2], ou[3]);
@@ -91,10 +80,7 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
                 *reinterpret_cast<float4 *>(b + 4) = *reinterpret_cast<const float4 *>(x + D / 2 + 4);
                 float r[8], t[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    r[j] = a[j] * cs[j] - b[j] * sn[j];
-                    t[j] = b[j] * cs[j] + a[j] * sn[j];
-                }
+                for (int j = 0; j < 8; ++j) rope_rotate(a[j], b[j], cs[j], sn[j], r[j], t[j]);
                 *reinterpret_cast<float4 *>(x) = *reinterpret_cast<const float4 *>(r);
                 *reinterpret_cast<float4 *>(x + 4) = *reinterpret_cast<const float4 *>(r + 4);
                 *reinterpret_cast<float4 *>(x + D / 2) = *reinterpret_cast<const float4 *>(t);
@@ -102,6 +88,45 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
             }
         }
     }
+}
+
+// cos/sin table for the query rotation fused into the bf16 attention kernel: entry e holds, for
+// every pair index i, (cos, sin) of the angle of packed row row_of_entry[e] (e itself when
+// row_of_entry is NULL).  Same arithmetic as rope_kernel, so a query rotated from the table gets the
+// bits pevlm_rope_seq would have stored.  One thread per (entry, 8 pair indices).
+template <int D>
+__global__ __launch_bounds__(256) void rope_table_kernel(float2 *table, const int32_t *row_of_entry, SeqTable tab, RopeFreq fr,
+                                                         int32_t entry_begin, int32_t entry_end)
+{
+    constexpr int LANES_PER_ENTRY = D / 16;
+    const int32_t e = entry_begin + (blockIdx.x * 256 + threadIdx.x) / LANES_PER_ENTRY;
+    if (e >= entry_end) return;
+    const int32_t i0 = (threadIdx.x % LANES_PER_ENTRY) * 8;
+    const int32_t row = row_of_entry ? row_of_entry[e] : e;
+    int32_t s = 0;
+    while (s + 1 < tab.num_seqs && row >= tab.start[s + 1]) ++s;
+    const double pos = (double)(row - tab.start[s] + tab.pos_offset[s]);
+    float2 *dst = table + (int64_t)e * (D / 2) + i0;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+        float c0, s0, c1, s1;
+        rope_cos_sin<false>(pos, fr.inv_freq[i0 + j], c0, s0);
+        rope_cos_sin<false>(pos, fr.inv_freq[i0 + j + 1], c1, s1);
+        *reinterpret_cast<float4 *>(dst + j) = make_float4(c0, s0, c1, s1);
+    }
+}
+
+hipError_t launch_rope_table(float *table, const int32_t *row_of_entry, const SeqTable &tab, int32_t D, double rope_base,
+                             int32_t entry_begin, int32_t entry_end, hipStream_t stream)
+{
+    if (entry_end <= entry_begin) return hipSuccess;
+    RopeFreq fr;
+    for (int i = 0; i < 64; ++i) fr.inv_freq[i] = i < D / 2 ? pow(rope_base, -2.0 * (double)i / (double)D) : 0.0;
+    const int32_t per_block = 256 / (D / 16);
+    dim3 grid((entry_end - entry_begin + per_block - 1) / per_block);
+    if (D == 128) hipLaunchKernelGGL((rope_table_kernel<128>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end);
+    else hipLaunchKernelGGL((rope_table_kernel<64>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end);
+    return hipGetLastError();
 }
 
 static void fill_freq(RopeFreq &fr, int32_t D, double rope_base)
@@ -112,7 +137,7 @@ static void fill_freq(RopeFreq &fr, int32_t D, double rope_base)
 template <bool MROPE>
 static hipError_t launch_rope_any(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
                                   double rope_base, int32_t row_begin, int32_t row_end, const int32_t *pos3, int64_t T,
-                                  int32_t sec0, int32_t sec01, hipStream_t stream)
+                                  int32_t sec0, int32_t sec01, float *table, hipStream_t stream)
 {
     RopeFreq fr;
     fill_freq(fr, D, rope_base);
@@ -120,7 +145,7 @@ static hipError_t launch_rope_any(void *q, void *k, const SeqTable &tab, int32_t
     int32_t tokens_per_block = 256 / (D / 16);
     dim3 grid((row_end - row_begin + tokens_per_block - 1) / tokens_per_block);
 #define PEVLM_ROPE_LAUNCH(DD, BB) \
-    hipLaunchKernelGGL((rope_kernel<DD, BB, MROPE>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end, pos3, T, sec0, sec01)
+    hipLaunchKernelGGL((rope_kernel<DD, BB, MROPE>), grid, dim3(256), 0, stream, q, k, tab, fr, Hq, Hkv, row_begin, row_end, pos3, T, sec0, sec01, (float2 *)table)
     if (D == 128 && bf16) PEVLM_ROPE_LAUNCH(128, true);
     else if (D == 128) PEVLM_ROPE_LAUNCH(128, false);
     else if (bf16) PEVLM_ROPE_LAUNCH(64, true);
@@ -130,19 +155,19 @@ static hipError_t launch_rope_any(void *q, void *k, const SeqTable &tab, int32_t
 }
 
 hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
-                       double rope_base, hipStream_t stream)
+                       double rope_base, float *table, hipStream_t stream)
 {
     int32_t n = tab.num_seqs;
     int32_t row_begin = tab.start[0];
     int32_t row_end = tab.start[n - 1] + tab.sink[n - 1] + tab.ctx[n - 1] + tab.query[n - 1];
-    return launch_rope_any<false>(q, k, tab, Hq, Hkv, D, bf16, rope_base, row_begin, row_end, nullptr, 0, 0, 0, stream);
+    return launch_rope_any<false>(q, k, tab, Hq, Hkv, D, bf16, rope_base, row_begin, row_end, nullptr, 0, 0, 0, table, stream);
 }
 
 hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
                              const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream)
 {
     SeqTable tab = {};
-    return launch_rope_any<true>(q, k, tab, Hq, Hkv, D, bf16, rope_base, 0, (int32_t)T, pos3, T, sec0, sec01, stream);
+    return launch_rope_any<true>(q, k, tab, Hq, Hkv, D, bf16, rope_base, 0, (int32_t)T, pos3, T, sec0, sec01, nullptr, stream);
 }
 
 }  // namespace pevlm

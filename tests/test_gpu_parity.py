@@ -307,3 +307,87 @@ def test_mrope_full_size_c3_sampled_rows(oracle):
         exact = oracle.rope_mrope(data[key], ids, (16, 24, 24), w.rope_base, rows=rows)
         err = np.abs(to_host_f32(t[idx]) - exact)
         assert np.all(err <= np.abs(exact) * 2.0 ** -8 + 1e-6)
+
+
+# ------------------------------------------------------------------------------------ fused query rotation
+FUSED_CASES = [
+    ("tiles_ragged", 8, 2, 128, [(300, 392, 1000, 70)], 0, None),
+    ("batch_mixed_offsets", 4, 2, 128, [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)], 3,
+     [7, 0, 100000, 31]),
+    ("d64", 4, 1, 64, [(100, 160, 500, 33)], 2, None),
+]
+
+
+@pytest.mark.parametrize("name,Hq,Hkv,D,seqs,splits,offs", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_fused_query_rotation_equals_unfused_bitwise_and_oracle(oracle, name, Hq, Hkv, D, seqs, splits, offs):
+    """pevlm_*_attn_rope on un-rotated q (+ K rotated alone) must reproduce the three-call path bit for
+    bit, and therefore the oracle within the bf16 tolerances; q itself stays untouched."""
+    w = W.Workload(name, 14, "bf16", Hq, Hkv, D, 1.0e6, seqs, 0.5, key_offset_scale=0.3)
+    data = W.generate(w)
+    ref = run_path(w, data, num_splits=splits, pos_offset=offs, want_lse=True)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    q_before = q.clone()
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((w.total_tokens, Hq), float("nan"), device=DEV)
+    # keys rotated in place by the prefill call itself
+    P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base, offs, lse=lse)
+    P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base, offs, num_splits=splits, lse=lse)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q_before)
+    assert torch.equal(k.view(torch.int16), ref["k_rot"].view(torch.int16))
+    assert torch.equal(out.view(torch.int16), ref["out"].view(torch.int16))
+    assert torch.equal(lse.view(torch.int32), ref["lse"].view(torch.int32))
+    # keys rotated beforehand by pevlm_rope_seq
+    k2 = to_device(data["k"])
+    out2 = torch.full_like(q, float("nan"))
+    P.pevlm_rope_seq(None, k2, lay, heads, w.rope_base, offs)
+    P.pevlm_block_prefill_attn_rope(q, k2, v, out2, lay, heads, w.rope_base, offs, k_is_rotated=True)
+    P.pevlm_query_attn_rope(q, k2, v, out2, lay, heads, w.rope_base, offs, num_splits=splits)
+    torch.cuda.synchronize()
+    assert torch.equal(k2.view(torch.int16), ref["k_rot"].view(torch.int16))
+    assert torch.equal(out2.view(torch.int16), ref["out"].view(torch.int16))
+    want, _ = oracle_rows(oracle, w, data, None, pos_offset=offs)
+    check_bf16(to_host_f32(out), want, name + "/fused")
+
+
+def test_fused_query_rotation_full_size_c3(oracle):
+    w = W.CONFIGS["c3"]
+    data = W.generate(w)
+    ref = run_path(w, data, poison=True)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.full_like(q, float("nan"))
+    P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+    P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), ref["out"].view(torch.int16))
+    rows = W.sample_rows(w, n_random=128, max_question_rows=16)
+    want, _ = oracle_rows(oracle, w, data, rows)
+    check_bf16(to_host_f32(out[torch.from_numpy(rows).to(DEV)]), want, "c3/fused")
+
+
+def test_fused_query_rotation_rejects_fp32():
+    w = W.CONFIGS["c1"]
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.zeros_like(q)
+    with pytest.raises(P.PevlmError):
+        P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+    with pytest.raises(P.PevlmError):
+        P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+
+
+def test_fused_prefill_with_no_prefill_rows_still_rotates_keys():
+    w = W.small_variant(W.CONFIGS["c2"], "question_only_bf16", [(0, 1, 0, 70)])
+    data = W.generate(w)
+    ref = run_path(w, data)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.full_like(q, float("nan"))
+    P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+    P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+    torch.cuda.synchronize()
+    assert torch.equal(k.view(torch.int16), ref["k_rot"].view(torch.int16))
+    assert torch.equal(out.view(torch.int16), ref["out"].view(torch.int16))
