@@ -391,3 +391,56 @@ def test_fused_prefill_with_no_prefill_rows_still_rotates_keys():
     torch.cuda.synchronize()
     assert torch.equal(k.view(torch.int16), ref["k_rot"].view(torch.int16))
     assert torch.equal(out.view(torch.int16), ref["out"].view(torch.int16))
+
+
+# ------------------------------------------------------------------------------------ many sequences
+def _many_seqs(n, seed):
+    rng = np.random.default_rng(seed)
+    seqs = []
+    for _ in range(n):
+        S, B = int(rng.integers(0, 40)), int(rng.integers(1, 50))
+        C = int(rng.integers(0, 120)) if rng.random() < 0.8 else 0
+        Q = int(rng.integers(0, 20))
+        if S + C + Q == 0:
+            Q = 1
+        seqs.append((S, B, C, Q))
+    return seqs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_batches_larger_than_one_sequence_table(oracle, dtype):
+    """130 packed sequences: the host hands the sequence table to the kernels in pieces of 48, so
+    work-list offsets, compact question rows and RoPE rows cross piece boundaries."""
+    seqs = _many_seqs(130, 5)
+    w = W.Workload("many_" + dtype, 15, dtype, 4, 2, 64 if dtype == "f32" else 128, 1.0e4, seqs, 1.0 if dtype == "f32" else 0.5)
+    data = W.generate(w)
+    offs = [int(x) for x in np.random.default_rng(6).integers(0, 5000, len(seqs))]
+    r = run_path(w, data, num_splits=2, pos_offset=offs, want_lse=True)
+    want, want_lse = oracle_rows(oracle, w, data, None, pos_offset=offs)
+    got = to_host_f32(r["out"])
+    if dtype == "f32":
+        assert np.isfinite(got).all() and np.max(np.abs(got - want)) <= F32_TOL
+        assert np.max(np.abs(to_host_f32(r["lse"]) - want_lse)) <= 1e-4
+    else:
+        check_bf16(got, want, "many_bf16")
+        lay, heads = layout_heads(w)
+        q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+        out = torch.full_like(q, float("nan"))
+        P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base, offs)
+        P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base, offs, num_splits=2)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), r["out"].view(torch.int16))
+    # device-built work lists equal the host enumeration across the pieces
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.zeros_like(q)
+    for ws, host in ((P.pevlm_block_prefill_attn(q, k, v, out, lay, heads),
+                      P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads))),
+                     (P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=3),
+                      P.pevlm_query_worklist_host(lay, P.pevlm_query_tile_rows(heads), 3))):
+        torch.cuda.synchronize()
+        n = len(host)
+        assert n > 100
+        dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
+        host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
+        assert np.array_equal(dev_items, host_items)
