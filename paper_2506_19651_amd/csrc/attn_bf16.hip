@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     const int32_t item_idx = p.n_items - 1 - rest % p.n_items;
     const int32_t hs = (rest / p.n_items) * heads_inner + inner;
     const pevlm_work_item it = p.items[item_idx];
-    const int32_t g = p.heads.kv_of_q[p.heads.head_order[hs]];
+    const int32_t g = __builtin_amdgcn_readfirstlane((int32_t)p.heads.kv_of_q[p.heads.head_order[hs]]);  // workgroup-uniform
     const int32_t Hq = p.n_q_heads, Hkv = p.n_kv_heads;
 
     const int32_t tid = threadIdx.x, lane = tid & 63;
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
     if (hpw > 1 && (inner % hpw) != 0) return;
     const int32_t slot = hpw > 1 ? inner + wave / wph : inner;
     const bool head_ok = slot < heads_inner;
-    const int32_t h = p.heads.head_order[hs - inner + (head_ok ? slot : inner)];
+    const int32_t h = __builtin_amdgcn_readfirstlane((int32_t)p.heads.head_order[hs - inner + (head_ok ? slot : inner)]);  // wavefront-uniform
     const int32_t rg = hpw > 1 ? wave % wph : wave;  // this wave's group of 32 rows
     const int32_t l32 = lane & 31, g32 = lane >> 5;
     const uint16_t *Q = (const uint16_t *)p.q, *K = (const uint16_t *)p.k, *V = (const uint16_t *)p.v;
