@@ -25,6 +25,23 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
     int32_t tok = row_begin + blockIdx.x * TOKENS_PER_BLOCK + threadIdx.x / LANES_PER_TOKEN;
     if (tok >= row_end) return;
     int32_t i0 = (threadIdx.x % LANES_PER_TOKEN) * 8;
+    // bf16: the first rows of the token are requested before the angles are formed, and each row is
+    // requested four rows ahead of its use, so that the sine/cosine arithmetic and the rotation run
+    // under the memory latency.  Rows of the token: its Hq query heads, then its Hkv key heads.
+    constexpr int PF = 4;
+    const int32_t nq = q ? Hq : 0, nrows = nq + (k ? Hkv : 0);
+    uint16_t *const qrow = (uint16_t *)q + ((int64_t)tok * Hq) * D + i0;
+    uint16_t *const krow = (uint16_t *)k + ((int64_t)tok * Hkv) * D + i0;
+    uint4 plo[PF], phi[PF];
+    if (BF16) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (j < nrows) {
+                const uint16_t *x = j < nq ? qrow + (int64_t)j * D : krow + (int64_t)(j - nq) * D;
+                plo[j] = *reinterpret_cast<const uint4 *>(x);
+                phi[j] = *reinterpret_cast<const uint4 *>(x + D / 2);
+            }
+    }
     double pos = 0.0, pos_axis[3] = {0.0, 0.0, 0.0};
     if (MROPE) {
 #pragma unroll
@@ -45,32 +62,43 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
 #pragma unroll
         for (int j = 0; j < 8; j += 2) *reinterpret_cast<float4 *>(dst + j) = make_float4(cs[j], sn[j], cs[j + 1], sn[j + 1]);
     }
-    for (int pass = 0; pass < 2; ++pass) {
-        void *base = pass == 0 ? q : k;
-        int32_t H = pass == 0 ? Hq : Hkv;
-        if (!base) continue;
-        if (BF16) {
-            uint16_t *x = (uint16_t *)base + ((int64_t)tok * H) * D + i0;
-#pragma unroll 4
-            for (int32_t h = 0; h < H; ++h, x += D) {
-                uint4 lo = *reinterpret_cast<const uint4 *>(x);
-                uint4 hi = *reinterpret_cast<const uint4 *>(x + D / 2);
+    if (BF16) {
+        for (int32_t r0 = 0; r0 < nrows; r0 += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                const int32_t r = r0 + j;
+                if (r >= nrows) break;
+                uint16_t *x = r < nq ? qrow + (int64_t)r * D : krow + (int64_t)(r - nq) * D;
+                const uint4 lo = plo[j], hi = phi[j];
+                if (r + PF < nrows) {
+                    const int32_t rn = r + PF;
+                    const uint16_t *xn = rn < nq ? qrow + (int64_t)rn * D : krow + (int64_t)(rn - nq) * D;
+                    plo[j] = *reinterpret_cast<const uint4 *>(xn);
+                    phi[j] = *reinterpret_cast<const uint4 *>(xn + D / 2);
+                }
                 uint32_t l[4] = {lo.x, lo.y, lo.z, lo.w}, u[4] = {hi.x, hi.y, hi.z, hi.w};
                 uint32_t ol[4], ou[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     float a0 = __uint_as_float(l[w] << 16), a1 = __uint_as_float(l[w] & 0xffff0000u);
                     float b0 = __uint_as_float(u[w] << 16), b1 = __uint_as_float(u[w] & 0xffff0000u);
-                    float r0, r1, t0, t1;
-                    rope_rotate(a0, b0, cs[2 * w], sn[2 * w], r0, t0);
-                    rope_rotate(a1, b1, cs[2 * w + 1], sn[2 * w + 1], r1, t1);
-                    ol[w] = rope_pack_bf16(r0, r1);
-                    ou[w] = rope_pack_bf16(t0, t1);
+                    float r0f, r1f, t0f, t1f;
+                    rope_rotate(a0, b0, cs[2 * w], sn[2 * w], r0f, t0f);
+                    rope_rotate(a1, b1, cs[2 * w + 1], sn[2 * w + 1], r1f, t1f);
+                    ol[w] = rope_pack_bf16(r0f, r1f);
+                    ou[w] = rope_pack_bf16(t0f, t1f);
                 }
                 *reinterpret_cast<uint4 *>(x) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
                 *reinterpret_cast<uint4 *>(x + D / 2) = make_uint4(ou[0], ou[1], ou[2], ou[3]);
             }
-        } else {
+        }
+        return;
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+        void *base = pass == 0 ? q : k;
+        int32_t H = pass == 0 ? Hq : Hkv;
+        if (!base) continue;
+        {
             float *x = (float *)base + ((int64_t)tok * H) * D + i0;
             for (int32_t h = 0; h < H; ++h, x += D) {
                 float a[8], b[8];
