@@ -444,3 +444,56 @@ def test_batches_larger_than_one_sequence_table(oracle, dtype):
         dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
         host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
         assert np.array_equal(dev_items, host_items)
+
+
+# ------------------------------------------------------------------------------------ seeded sweep
+def _random_case(rng):
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 7]))
+    n_seq = int(rng.integers(1, 4))
+    seqs = []
+    for _ in range(n_seq):
+        S = int(rng.choice([0, 1, 31, 64, 65, 130, 200]))
+        B = int(rng.choice([1, 7, 32, 64, 100, 128, 129, 300]))
+        C = int(rng.choice([0, B, 2 * B, 2 * B + 1, 3 * B - 1, 333])) if rng.random() < 0.85 else 0
+        C = min(C, 500)
+        Q = int(rng.choice([0, 1, 5, 32, 33, 64, 65, 129, 140]))
+        if S + C + Q == 0:
+            S = 3
+        seqs.append((S, B, C, Q))
+    hmap = None
+    if rng.random() < 0.25:
+        hmap = [int(x) for x in rng.integers(0, Hkv, Hkv * G)]
+    return D, Hkv, G, seqs, hmap, int(rng.integers(0, 6))
+
+
+@pytest.mark.parametrize("dtype,seed", [("bf16", 101), ("bf16", 102), ("bf16", 103), ("f32", 104), ("bf16", 105), ("bf16", 106), ("f32", 107), ("bf16", 108)])
+def test_seeded_sweep_of_small_layouts(oracle, dtype, seed):
+    """Twelve random small layouts per seed (ragged tiles, 1-token blocks, missing regions, GQA widths
+    1/2/4/7, explicit head maps, split counts 0-5) through all three calls, every row against the
+    oracle; the bf16 cases also through the calls with RoPE folded in."""
+    rng = np.random.default_rng(seed)
+    for case in range(12):
+        D, Hkv, G, seqs, hmap, splits = _random_case(rng)
+        tag = f"{dtype}/{seed}/{case}: D={D} Hq={Hkv * G} Hkv={Hkv} seqs={seqs} map={hmap} splits={splits}"
+        print(tag, flush=True)
+        w = W.Workload(f"sweep{seed}_{case}", 16, dtype, Hkv * G, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0,
+                       key_offset_scale=0.2)
+        data = W.generate(w)
+        r = run_path(w, data, num_splits=splits, kv_head_of_q=hmap, want_lse=True)
+        want, want_lse = oracle_rows(oracle, w, data, None, kv_head_of_q=hmap)
+        got = to_host_f32(r["out"])
+        if dtype == "f32":
+            assert np.isfinite(got).all() and np.max(np.abs(got - want)) <= F32_TOL, tag
+            assert np.max(np.abs(to_host_f32(r["lse"]) - want_lse)) <= 1e-4, tag
+            continue
+        check_bf16(got, want, tag)
+        assert np.max(np.abs(to_host_f32(r["lse"]) - want_lse)) <= 2e-2, tag
+        lay, heads = layout_heads(w, hmap)
+        q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+        out = torch.full_like(q, float("nan"))
+        P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+        P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base, num_splits=splits)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), r["out"].view(torch.int16)), tag
