@@ -27,7 +27,9 @@
  * Parity pins (all under tests/, none of them calls back into this file for the expected value):
  * brute-force Python loops that evaluate Eq. 3, 4, 5 one by one on gathered keys; torch's CPU
  * scaled_dot_product_attention on the gathered causal pieces; the closed-form pair counts of
- * Eq. 6-10; convexity / constant-V / zero-Q closed forms; RoPE analytic identities.
+ * Eq. 6-10; convexity / constant-V / zero-Q closed forms; RoPE analytic identities; for the two
+ * extensions (three-axis RoPE, sliding window for the question) a complex-multiplication brute
+ * force / the rule written out entry by entry and library causal attention over the kept keys.
  * The paper prints no numeric worked example, so value-level parity with the authors' own
  * implementation is unpinned; every function here is pinned by the checks above instead.
  *
@@ -48,6 +50,10 @@ typedef struct {
     const int32_t *block_len;  /* B per sequence */
     const int32_t *ctx_len;    /* C per sequence: total context tokens, last block may be short */
     const int32_t *query_len;  /* Q per sequence */
+    /* Sliding window for the question (the paper's outlook, Sec. "Conclusion": discard the oldest
+     * video blocks): NULL, or per sequence the number W of most recent context blocks a question
+     * row still sees besides the sink and the question itself; W < 0 = all blocks. */
+    const int32_t *window_blocks;
 } oracle_layout;
 
 static double widen(const void *base, int dtype, int64_t idx)
@@ -127,6 +133,14 @@ void pevlm_oracle_mask_row(const oracle_layout *lay, int64_t t, int causal, uint
     for (int64_t j = 0; j < L; ++j)
         vis[base + j] = (uint8_t)(causal ? pevlm_oracle_visible(S, B, C, t - base, j)
                                          : pevlm_oracle_visible_blockwise(S, B, C, Q, t - base, j));
+    /* sliding window: a question row loses the context blocks older than the last W */
+    if (lay->window_blocks && lay->window_blocks[s] >= 0 && t - base >= S + C) {
+        int64_t n_blocks = (C + B - 1) / B;
+        int64_t first_kept = n_blocks - lay->window_blocks[s];
+        if (first_kept < 0) first_kept = 0;
+        for (int64_t j = S; j < S + C; ++j)
+            if ((j - S) / B < first_kept) vis[base + j] = 0;
+    }
 }
 
 /* Sequential positions (Sec. "Position Encoding"): pos[t] = index of token t inside its own

@@ -39,6 +39,7 @@ class _CLayout(ctypes.Structure):
         ("block_len", ctypes.POINTER(ctypes.c_int32)),
         ("ctx_len", ctypes.POINTER(ctypes.c_int32)),
         ("query_len", ctypes.POINTER(ctypes.c_int32)),
+        ("window_blocks", ctypes.POINTER(ctypes.c_int32)),
     ]
 
 
@@ -74,6 +75,7 @@ class Layout:
     block_len: Sequence[int]
     ctx_len: Sequence[int]
     query_len: Sequence[int]
+    window_blocks: Optional[Sequence[int]] = None  # question sees sink + last W blocks (None / <0: all)
 
     def __post_init__(self):
         self._cu = np.ascontiguousarray(self.cu_seqlens, dtype=np.int32)
@@ -82,7 +84,9 @@ class Layout:
         self._c = np.ascontiguousarray(self.ctx_len, dtype=np.int32)
         self._q = np.ascontiguousarray(self.query_len, dtype=np.int32)
         p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
-        self._c_struct = _CLayout(len(self._s), p(self._cu), p(self._s), p(self._b), p(self._c), p(self._q))
+        self._w = None if self.window_blocks is None else np.ascontiguousarray(self.window_blocks, dtype=np.int32)
+        self._c_struct = _CLayout(len(self._s), p(self._cu), p(self._s), p(self._b), p(self._c), p(self._q),
+                                  None if self._w is None else p(self._w))
 
     @property
     def num_seqs(self) -> int:

@@ -25,6 +25,11 @@ MUTATIONS = [
     ("softmax_not_normalised", "for (int32_t d = 0; d < D; ++d) o[d] /= l;", "for (int32_t d = 0; d < D; ++d) o[d] /= (l + 1e-3);"),
     ("value_index", "int64_t v0 = (j * Hkv + g) * (int64_t)D;", "int64_t v0 = (j * Hkv + (Hkv - 1 - g)) * (int64_t)D;"),
     ("lse_dropped_log", "lse[r * Hq + h] = m + log(l);", "lse[r * Hq + h] = m;"),
+    ("window_keeps_oldest_instead_of_newest", "if ((j - S) / B < first_kept) vis[base + j] = 0;",
+     "if ((j - S) / B >= lay->window_blocks[s]) vis[base + j] = 0;"),
+    ("window_off_by_one_block", "int64_t first_kept = n_blocks - lay->window_blocks[s];",
+     "int64_t first_kept = n_blocks - lay->window_blocks[s] - 1;"),
+    ("window_applied_to_context_rows", "lay->window_blocks[s] >= 0 && t - base >= S + C) {", "lay->window_blocks[s] >= 0 && t - base >= S) {"),
     ("mrope_section_boundary", "int axis = i < section[0] ? 0 :", "int axis = i <= section[0] ? 0 :"),
     ("mrope_axes_swapped", "(i < section[0] + section[1] ? 1 : 2);", "(i < section[0] + section[1] ? 2 : 1);"),
     ("mrope_sign", "o[i] = lo * ca - hi * sa;", "o[i] = lo * ca + hi * sa;"),

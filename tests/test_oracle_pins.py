@@ -421,6 +421,64 @@ def test_p11_mrope_position_ids_of_a_video_prompt():
     np.testing.assert_array_equal(ids[:, 40:42], np.tile(5 + np.arange(2), (3, 1)))  # largest id was 2 + 2 (column)
 
 
+# ------------------------------------------------------------------ sliding window for the question
+def make_window_layout(oracle, seqs, windows):
+    lens = [s + c + q for (s, b, c, q) in seqs]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    a = np.asarray(seqs).reshape(-1, 4)
+    return oracle.Layout(cu, a[:, 0], a[:, 1], a[:, 2], a[:, 3], window_blocks=windows)
+
+
+@pytest.mark.parametrize("seqs,windows", [
+    ([(3, 4, 14, 5)], [2]), ([(3, 4, 14, 5)], [0]), ([(0, 5, 15, 4)], [1]), ([(6, 3, 9, 2)], [9]),
+    ([(2, 4, 9, 3), (5, 2, 8, 0), (1, 3, 3, 4)], [1, 0, -1]),
+])
+def test_p12_window_mask_against_explicit_rule(oracle, seqs, windows):
+    """Mask matrix with a window, entry by entry, against the rule written out here: rows outside the
+    question are unchanged; a question row keeps a context key only if its block is among the last W."""
+    lay_w = make_window_layout(oracle, seqs, windows)
+    lay = make_layout(oracle, seqs)
+    Mw, M = oracle.mask_matrix(lay_w), oracle.mask_matrix(lay)
+    t0 = 0
+    for (S, B, C, Q), W_ in zip(seqs, windows):
+        L = S + C + Q
+        n_blocks = -(-C // B) if C else 0
+        for i in range(L):
+            for j in range(L):
+                want = int(M[t0 + i, t0 + j])
+                if W_ >= 0 and i >= S + C and S <= j < S + C and (j - S) // B < n_blocks - W_:
+                    want = 0
+                assert int(Mw[t0 + i, t0 + j]) == want, (i, j)
+        # nothing leaks across sequences either
+        assert not Mw[t0:t0 + L, :t0].any() and not Mw[t0:t0 + L, t0 + L:].any()
+        t0 += L
+
+
+@pytest.mark.parametrize("S,B,C,Q,W_", [(6, 4, 14, 5, 2), (0, 5, 15, 4, 1), (7, 3, 9, 3, 0), (4, 8, 20, 6, 1)])
+def test_p12_windowed_question_equals_causal_attention_over_kept_keys(oracle, S, B, C, Q, W_):
+    """Question rows under a window = the last Q rows of ordinary causal attention (torch CPU) over
+    [sink ; last W blocks ; question], every token rotated at its ORIGINAL position.  Sink and
+    context rows are those of the method without a window."""
+    Hq, Hkv, D, base = 4, 2, 16, 1.0e4
+    L = S + C + Q
+    lay_w = make_window_layout(oracle, [(S, B, C, Q)], [W_])
+    q, k, v = rand_qkv(L, Hq, Hkv, D)
+    got, _ = oracle.forward(q, k, v, lay_w, base)
+    plain, _ = oracle.forward(q, k, v, make_layout(oracle, [(S, B, C, Q)]), base)
+    np.testing.assert_array_equal(got[:S + C], plain[:S + C])
+    pos = np.arange(L, dtype=np.float64)
+    qr, kr = brute_rope_complex(q, pos, base), brute_rope_complex(k, pos, base)
+    n_blocks = -(-C // B)
+    first_kept = max(0, n_blocks - W_)
+    idx = np.r_[0:S, S + first_kept * B:S + C, S + C:L]
+    np.testing.assert_allclose(got[S + C:], sdpa_last_rows(qr[idx], kr[idx], v[idx], Q, Hq, Hkv), atol=1e-10, rtol=0)
+    # a window that covers every block changes nothing; lse of a windowed row is never larger
+    full, lse_full = oracle.forward(q, k, v, make_window_layout(oracle, [(S, B, C, Q)], [n_blocks]), base)
+    np.testing.assert_array_equal(full, plain)
+    _, lse_w = oracle.forward(q, k, v, lay_w, base)
+    assert np.all(lse_w[S + C:] <= lse_full[S + C:] + 1e-12)
+
+
 # ------------------------------------------------------------------ log-sum-exp merge identity
 def test_p8_lse_merge_identity(oracle):
     seqs = [(6, 7, 20, 5)]
