@@ -237,6 +237,18 @@ def main():
         result["ms_query_attn_cold"] = round(float(np.median(cold)), 4)
         result["query_kv_gbs_cold"] = round(kv_bytes / (float(np.median(cold)) * 1e-3) / 1e9, 1)
         del src, dst
+        # streaming calls: one more context block appended to the prompt (rows of the last block only),
+        # and the question restricted to the sink plus the newest quarter of the blocks
+        nblk = [(-(-c // b) if c else 0) for (_s, b, c, _q) in w.seqs]
+        if min(nblk) >= 4:
+            first, one = [n - 1 for n in nblk], [1] * len(nblk)
+            ms_blk = timed(lambda: P.pevlm_block_prefill_attn_blocks(q, k, v, out, lay, heads, first, one, False,
+                                                                     workspace=ws_p, stream=stream), 10)
+            win = [n // 4 for n in nblk]
+            ws_w = torch.empty(P.pevlm_query_window_workspace_bytes(lay, heads, 0), dtype=torch.uint8, device=dev)
+            ms_win = timed(lambda: P.pevlm_query_attn_window(q, k, v, out, lay, heads, win, workspace=ws_w, stream=stream), 10)
+            result["streaming"] = {"ms_prefill_one_appended_block_per_sequence": round(ms_blk, 4),
+                                   "ms_query_attn_window_quarter": round(ms_win, 4), "window_blocks": win}
         # three-axis RoPE on the same tensors (ids of a video prompt with 16x16 / 14x14 tokens per frame)
         ft, gw = (196, 14) if w.seqs[0][1] % 196 == 0 else (256, 16)
         ids = torch.from_numpy(W.mrope_position_ids(w, ft, gw)).to(dev)

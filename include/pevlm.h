@@ -155,6 +155,33 @@ pevlm_status pevlm_query_attn_rope(const void *q, const void *k, const void *v, 
                                    double rope_base, const int32_t *pos_offset, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
+/*
+ * Streaming use (the paper's outlook, Sec. "Conclusion": streaming video, a sliding window that
+ * discards the oldest video blocks).  Both calls work on the ordinary packed layout; blocks that
+ * are no longer referenced are simply never read, so the caller may recycle their storage.
+ *
+ * pevlm_block_prefill_attn_blocks: as pevlm_block_prefill_attn, restricted per sequence to the rows
+ * of context blocks first_block[s] .. first_block[s] + num_blocks[s] - 1 (HOST arrays [num_seqs];
+ * the range must lie inside the sequence's ceil(C/B) blocks, num_blocks[s] may be 0) and, if
+ * with_sink != 0, the sink rows.  By Eq. 4 a block needs only the sink's and its own K/V, so
+ * appending blocks to a prompt costs the new blocks' rows only.  Rows outside the selection are
+ * not touched.  Workspace: pevlm_block_prefill_workspace_bytes.
+ *
+ * pevlm_query_attn_window: as pevlm_query_attn, but a question row of sequence s sees, besides the
+ * sink and the question itself, only the last window_blocks[s] context blocks (HOST [num_seqs];
+ * a negative entry = all blocks; 0 = none).  The sink is always processed as a split of its own and
+ * the remaining keys are cut into num_splits - 1 runs, so at least 2 splits are used (num_splits == 1
+ * is raised to 2; 0 = chosen by the library).  Workspace: pevlm_query_window_workspace_bytes.
+ */
+pevlm_status pevlm_block_prefill_attn_blocks(const void *q, const void *k, const void *v, void *out, float *lse,
+                                             const pevlm_layout *layout, const pevlm_heads *heads,
+                                             const int32_t *first_block, const int32_t *num_blocks, int32_t with_sink,
+                                             void *workspace, size_t workspace_bytes, void *stream);
+size_t pevlm_query_window_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits);
+pevlm_status pevlm_query_attn_window(const void *q, const void *k, const void *v, void *out, float *lse,
+                                     const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *window_blocks,
+                                     int32_t num_splits, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Message of the last failure on the calling thread (static storage, never NULL). */
 const char *pevlm_last_error(void);
 /* Library version: major * 10000 + minor * 100 + patch. */
@@ -187,6 +214,13 @@ int64_t pevlm_prefill_worklist_host(const pevlm_layout *layout, int32_t tile_row
  * first row of the item in the partial buffers. */
 int64_t pevlm_query_worklist_host(const pevlm_layout *layout, int32_t tile_rows, int32_t num_splits,
                                   pevlm_work_item *items, int64_t capacity);
+/* The same enumerations for the streaming calls: prefill items of the selected blocks (and the sink
+ * if with_sink != 0); question items under a window (num_splits >= 2: split 0 is the sink). */
+int64_t pevlm_prefill_worklist_blocks_host(const pevlm_layout *layout, int32_t tile_rows, const int32_t *first_block,
+                                           const int32_t *num_blocks, int32_t with_sink, pevlm_work_item *items,
+                                           int64_t capacity);
+int64_t pevlm_query_worklist_window_host(const pevlm_layout *layout, int32_t tile_rows, int32_t num_splits,
+                                         const int32_t *window_blocks, pevlm_work_item *items, int64_t capacity);
 /* Visible (query, key) pairs per head implied by the layout, split by region; the causal closed
  * forms behind the paper's operation counts (Eq. 6-10).  Any output pointer may be NULL.
  * Returns PEVLM_OK or PEVLM_ERR_INVALID_ARG. */

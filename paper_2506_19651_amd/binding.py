@@ -76,6 +76,17 @@ def load_library():
         lib.pevlm_query_rope_workspace_bytes.argtypes = [LP, HP, i32]
         lib.pevlm_query_attn_rope.restype = ctypes.c_int
         lib.pevlm_query_attn_rope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, ctypes.c_double, vp, vp, ctypes.c_size_t, vp]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.pevlm_block_prefill_attn_blocks.restype = ctypes.c_int
+        lib.pevlm_block_prefill_attn_blocks.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32p, i32p, i32, vp, ctypes.c_size_t, vp]
+        lib.pevlm_query_window_workspace_bytes.restype = ctypes.c_size_t
+        lib.pevlm_query_window_workspace_bytes.argtypes = [LP, HP, i32]
+        lib.pevlm_query_attn_window.restype = ctypes.c_int
+        lib.pevlm_query_attn_window.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32p, i32, vp, ctypes.c_size_t, vp]
+        lib.pevlm_prefill_worklist_blocks_host.restype = ctypes.c_int64
+        lib.pevlm_prefill_worklist_blocks_host.argtypes = [LP, i32, i32p, i32p, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
+        lib.pevlm_query_worklist_window_host.restype = ctypes.c_int64
+        lib.pevlm_query_worklist_window_host.argtypes = [LP, i32, i32, i32p, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_last_error.restype = ctypes.c_char_p
         lib.pevlm_version.restype = i32
         lib.pevlm_prefill_tile_rows.restype = i32
@@ -267,6 +278,61 @@ def pevlm_query_attn(q, k, v, out, layout: Layout, heads: Heads, num_splits: int
                                            heads.ref(), int(num_splits), _ptr(workspace), workspace.numel(),
                                            _stream_ptr(stream)))
     return workspace
+
+
+def _i32_array(values):
+    a = np.ascontiguousarray(values, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def pevlm_block_prefill_attn_blocks(q, k, v, out, layout: Layout, heads: Heads, first_block, num_blocks, with_sink: bool,
+                                    lse=None, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_block_prefill_workspace_bytes(layout, heads), q)
+    _fb, fbp = _i32_array(first_block)
+    _nb, nbp = _i32_array(num_blocks)
+    _check(load_library().pevlm_block_prefill_attn_blocks(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
+                                                          heads.ref(), fbp, nbp, int(bool(with_sink)), _ptr(workspace),
+                                                          workspace.numel(), _stream_ptr(stream)))
+    return workspace
+
+
+def pevlm_query_window_workspace_bytes(layout: Layout, heads: Heads, num_splits: int = 0) -> int:
+    return int(load_library().pevlm_query_window_workspace_bytes(layout.ref(), heads.ref(), int(num_splits)))
+
+
+def pevlm_query_attn_window(q, k, v, out, layout: Layout, heads: Heads, window_blocks, num_splits: int = 0, lse=None,
+                            workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_query_window_workspace_bytes(layout, heads, num_splits), q)
+    _w, wp = _i32_array(window_blocks)
+    _check(load_library().pevlm_query_attn_window(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(), heads.ref(),
+                                                  wp, int(num_splits), _ptr(workspace), workspace.numel(),
+                                                  _stream_ptr(stream)))
+    return workspace
+
+
+def pevlm_prefill_worklist_blocks_host(layout: Layout, tile_rows: int, first_block, num_blocks, with_sink: bool):
+    lib = load_library()
+    _fb, fbp = _i32_array(first_block)
+    _nb, nbp = _i32_array(num_blocks)
+    n = lib.pevlm_prefill_worklist_blocks_host(layout.ref(), tile_rows, fbp, nbp, int(bool(with_sink)), None, 0)
+    if n < 0:
+        raise PevlmError(PEVLM_ERR_INVALID_ARG, pevlm_last_error())
+    items = (WorkItem * max(n, 1))()
+    lib.pevlm_prefill_worklist_blocks_host(layout.ref(), tile_rows, fbp, nbp, int(bool(with_sink)), items, n)
+    return [items[i] for i in range(n)]
+
+
+def pevlm_query_worklist_window_host(layout: Layout, tile_rows: int, num_splits: int, window_blocks):
+    lib = load_library()
+    _w, wp = _i32_array(window_blocks)
+    n = lib.pevlm_query_worklist_window_host(layout.ref(), tile_rows, num_splits, wp, None, 0)
+    if n < 0:
+        raise PevlmError(PEVLM_ERR_INVALID_ARG, pevlm_last_error())
+    items = (WorkItem * max(n, 1))()
+    lib.pevlm_query_worklist_window_host(layout.ref(), tile_rows, num_splits, wp, items, n)
+    return [items[i] for i in range(n)]
 
 
 def pevlm_prefill_worklist_host(layout: Layout, tile_rows: int):

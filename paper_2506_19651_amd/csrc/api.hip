@@ -85,12 +85,39 @@ static int32_t tile_rows_of(const pevlm_heads *h, bool /*query*/)
     return h->dtype == PEVLM_BF16 ? kTileRowsBf16 : kTileRowsF32;
 }
 
+// Streaming restrictions of a call (host arrays of num_seqs entries, NULL = no restriction).
+struct Restrict {
+    const int32_t *first_block = nullptr, *num_blocks = nullptr;  // prefill: context blocks computed
+    int32_t with_sink = 1;                                        // prefill: sink rows computed
+    const int32_t *window_blocks = nullptr;                       // question: last W blocks visible (<0: all)
+};
+
+static int32_t blocks_of(const pevlm_layout *lay, int32_t s)
+{
+    return lay->ctx_len[s] > 0 ? (lay->ctx_len[s] + lay->block_len[s] - 1) / lay->block_len[s] : 0;
+}
+
+static pevlm_status check_restrict(const pevlm_layout *lay, const Restrict &r)
+{
+    if ((r.first_block == nullptr) != (r.num_blocks == nullptr))
+        return fail(PEVLM_ERR_INVALID_ARG, "first_block and num_blocks must be given together");
+    if (r.first_block)
+        for (int32_t s = 0; s < lay->num_seqs; ++s)
+            if (r.first_block[s] < 0 || r.num_blocks[s] < 0 || (int64_t)r.first_block[s] + r.num_blocks[s] > blocks_of(lay, s))
+                return fail(PEVLM_ERR_INVALID_ARG, "block range [%d, %d + %d) outside the %d context blocks of sequence %d",
+                            r.first_block[s], r.first_block[s], r.num_blocks[s], blocks_of(lay, s), s);
+    return PEVLM_OK;
+}
+
 // Fills the chunk table for sequences [s0, s0 + n).
-static void fill_table(const pevlm_layout *lay, int32_t s0, int32_t n, const int32_t *pos_offset, SeqTable *t)
+static void fill_table(const pevlm_layout *lay, int32_t s0, int32_t n, const int32_t *pos_offset, SeqTable *t,
+                       const Restrict &r = Restrict())
 {
     memset(t, 0, sizeof *t);
     t->num_seqs = n;
     t->seq_index0 = s0;
+    t->sel_sink = r.with_sink ? 1 : 0;
+    t->windowed = r.window_blocks ? 1 : 0;
     for (int32_t i = 0; i < n; ++i) {
         int32_t s = s0 + i;
         t->start[i] = lay->cu_seqlens[s];
@@ -99,14 +126,21 @@ static void fill_table(const pevlm_layout *lay, int32_t s0, int32_t n, const int
         t->ctx[i] = lay->ctx_len[s];
         t->query[i] = lay->query_len[s];
         t->pos_offset[i] = pos_offset ? pos_offset[s] : 0;
+        t->sel_first[i] = r.first_block ? r.first_block[s] : 0;
+        t->sel_count[i] = r.num_blocks ? r.num_blocks[s] : blocks_of(lay, s);
+        int32_t hidden = 0;  // context blocks the question no longer sees
+        if (r.window_blocks && r.window_blocks[s] >= 0) hidden = std::max(0, blocks_of(lay, s) - r.window_blocks[s]);
+        t->win_start[i] = t->sink[i] + (int32_t)std::min<int64_t>((int64_t)hidden * t->block[i], t->ctx[i]);
     }
 }
 
-static int64_t count_prefill_items(const pevlm_layout *lay, int32_t tile_rows)
+static int64_t count_prefill_items(const pevlm_layout *lay, int32_t tile_rows, const Restrict &r = Restrict())
 {
     int64_t n = 0;
     for (int32_t s = 0; s < lay->num_seqs; ++s)
-        n += prefill_items_of_seq(lay->sink_len[s], lay->ctx_len[s] > 0 ? lay->block_len[s] : 1, lay->ctx_len[s], tile_rows);
+        n += prefill_items_of_seq_sel(lay->sink_len[s], lay->ctx_len[s] > 0 ? lay->block_len[s] : 1, lay->ctx_len[s], tile_rows,
+                                      r.first_block ? r.first_block[s] : 0, r.num_blocks ? r.num_blocks[s] : blocks_of(lay, s),
+                                      r.with_sink);
     return n;
 }
 
@@ -183,11 +217,14 @@ struct QueryPlan {
     size_t off_items, off_qrow, off_ml, off_acc, off_rope, bytes;
 };
 
-static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits, bool fuse_rope = false)
+static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32_t num_splits, bool fuse_rope = false,
+                            bool windowed = false)
 {
     QueryPlan p;
     p.tile_rows = tile_rows_of(h, true);
     p.num_splits = num_splits > 0 ? num_splits : auto_splits(lay, h);
+    // with a window the sink is a split of its own, the rest of the keys takes at least one more
+    if (windowed) p.num_splits = std::min(PEVLM_MAX_SPLITS, std::max(2, p.num_splits + (num_splits > 0 ? 0 : 1)));
     p.total_q = total_query_rows(lay);
     p.n_items = count_query_tiles(lay, p.tile_rows) * p.num_splits;
     size_t off = 0;
@@ -276,9 +313,11 @@ size_t pevlm_block_prefill_rope_workspace_bytes(const pevlm_layout *layout, cons
 static pevlm_status prefill_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                                  const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
                                  size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
-                                 const int32_t *pos_offset, bool rotate_k)
+                                 const int32_t *pos_offset, bool rotate_k, const Restrict &sel = Restrict())
 {
     pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    st = check_restrict(layout, sel);
     if (st != PEVLM_OK) return st;
     AttnParams p;
     memset(&p, 0, sizeof p);
@@ -291,7 +330,7 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
         return fail(PEVLM_ERR_UNSUPPORTED, "the fused query rotation exists for bf16 tensors only");
     if (fuse_rope && !(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
     int32_t tile_rows = tile_rows_of(heads, false);
-    int64_t n_items = count_prefill_items(layout, tile_rows);
+    int64_t n_items = count_prefill_items(layout, tile_rows, sel);
     if (n_items == 0) {  // no sink or context rows: nothing to attend, but the keys are still rotated if asked
         if (fuse_rope && rotate_k && layout->cu_seqlens[layout->num_seqs] > 0)
             return pevlm_rope_seq(nullptr, const_cast<void *>(k), layout, heads, rope_base, pos_offset, stream);
@@ -309,9 +348,10 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
     for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
         SeqTable tab;
         int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
-        fill_table(layout, s0, n, pos_offset, &tab);
+        fill_table(layout, s0, n, pos_offset, &tab, sel);
         for (int32_t i = 0; i < n; ++i)
-            tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], tile_rows);
+            tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq_sel(tab.sink[i], tab.block[i], tab.ctx[i], tile_rows,
+                                                                               tab.sel_first[i], tab.sel_count[i], tab.sel_sink);
         if (tab.item_base[n] > 0) {
             hipError_t e = launch_build_prefill_items(tab, tile_rows, items, offset, hs);
             if (e != hipSuccess) return hip_fail(e, "work-list builder launch");
@@ -346,6 +386,19 @@ pevlm_status pevlm_block_prefill_attn(const void *q, const void *k, const void *
     return prefill_impl(q, k, v, out, lse, layout, heads, workspace, workspace_bytes, stream, false, 0.0, nullptr, false);
 }
 
+pevlm_status pevlm_block_prefill_attn_blocks(const void *q, const void *k, const void *v, void *out, float *lse,
+                                             const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *first_block,
+                                             const int32_t *num_blocks, int32_t with_sink, void *workspace,
+                                             size_t workspace_bytes, void *stream)
+{
+    if (!first_block || !num_blocks) return fail(PEVLM_ERR_INVALID_ARG, "first_block and num_blocks must not be NULL");
+    Restrict sel;
+    sel.first_block = first_block;
+    sel.num_blocks = num_blocks;
+    sel.with_sink = with_sink;
+    return prefill_impl(q, k, v, out, lse, layout, heads, workspace, workspace_bytes, stream, false, 0.0, nullptr, false, sel);
+}
+
 pevlm_status pevlm_block_prefill_attn_rope(const void *q, void *k, const void *v, void *out, float *lse,
                                            const pevlm_layout *layout, const pevlm_heads *heads, double rope_base,
                                            const int32_t *pos_offset, int32_t k_is_rotated, void *workspace,
@@ -372,7 +425,7 @@ size_t pevlm_query_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_
 static pevlm_status query_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                                const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
                                void *workspace, size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
-                               const int32_t *pos_offset)
+                               const int32_t *pos_offset, const Restrict &sel = Restrict())
 {
     pevlm_status st = check_layout(layout);
     if (st != PEVLM_OK) return st;
@@ -388,7 +441,7 @@ static pevlm_status query_impl(const void *q, const void *k, const void *v, void
     if (fuse_rope && heads->dtype != PEVLM_BF16)
         return fail(PEVLM_ERR_UNSUPPORTED, "the fused query rotation exists for bf16 tensors only");
     if (fuse_rope && !(rope_base > 0.0)) return fail(PEVLM_ERR_INVALID_ARG, "rope_base must be positive");
-    QueryPlan plan = plan_query(layout, heads, num_splits, fuse_rope);
+    QueryPlan plan = plan_query(layout, heads, num_splits, fuse_rope, sel.window_blocks != nullptr);
     if (plan.total_q == 0) return PEVLM_OK;
     if (plan.n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
     if (!workspace || workspace_bytes < plan.bytes || ((uintptr_t)workspace & 255))
@@ -405,7 +458,7 @@ static pevlm_status query_impl(const void *q, const void *k, const void *v, void
     for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
         SeqTable tab;
         int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
-        fill_table(layout, s0, n, pos_offset, &tab);
+        fill_table(layout, s0, n, pos_offset, &tab, sel);
         const int32_t entry_begin = qrow_base;
         for (int32_t i = 0; i < n; ++i) {
             tab.item_base[i + 1] = tab.item_base[i] + query_tiles_of_seq(tab.query[i], plan.tile_rows) * plan.num_splits;
@@ -456,6 +509,23 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
     return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, false, 0.0, nullptr);
 }
 
+size_t pevlm_query_window_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)
+{
+    if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
+    if (num_splits < 0 || num_splits > PEVLM_MAX_SPLITS) return 0;
+    return plan_query(layout, heads, num_splits, false, true).bytes + 256;
+}
+
+pevlm_status pevlm_query_attn_window(const void *q, const void *k, const void *v, void *out, float *lse,
+                                     const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *window_blocks,
+                                     int32_t num_splits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!window_blocks) return fail(PEVLM_ERR_INVALID_ARG, "window_blocks must not be NULL");
+    Restrict sel;
+    sel.window_blocks = window_blocks;
+    return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, false, 0.0, nullptr, sel);
+}
+
 pevlm_status pevlm_query_attn_rope(const void *q, const void *k, const void *v, void *out, float *lse,
                                    const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits, double rope_base,
                                    const int32_t *pos_offset, void *workspace, size_t workspace_bytes, void *stream)
@@ -494,6 +564,60 @@ int64_t pevlm_query_worklist_host(const pevlm_layout *layout, int32_t tile_rows,
             if (items && n < capacity)
                 items[n] = query_item(layout->cu_seqlens[s], layout->sink_len[s], layout->ctx_len[s], layout->query_len[s],
                                       tile_rows, num_splits, i, s, qrow_base, (int32_t)total_q, kKeyTile);
+        qrow_base += layout->query_len[s];
+    }
+    return n;
+}
+
+int64_t pevlm_prefill_worklist_blocks_host(const pevlm_layout *layout, int32_t tile_rows, const int32_t *first_block,
+                                           const int32_t *num_blocks, int32_t with_sink, pevlm_work_item *items,
+                                           int64_t capacity)
+{
+    if (check_layout(layout) != PEVLM_OK) return -1;
+    if (tile_rows < 1) { fail(PEVLM_ERR_INVALID_ARG, "tile_rows must be >= 1"); return -1; }
+    Restrict sel;
+    sel.first_block = first_block;
+    sel.num_blocks = num_blocks;
+    sel.with_sink = with_sink;
+    if (!first_block || !num_blocks || check_restrict(layout, sel) != PEVLM_OK) {
+        if (!first_block || !num_blocks) fail(PEVLM_ERR_INVALID_ARG, "first_block and num_blocks must not be NULL");
+        return -1;
+    }
+    int64_t n = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        int32_t B = layout->ctx_len[s] > 0 ? layout->block_len[s] : 1;
+        int32_t cnt = prefill_items_of_seq_sel(layout->sink_len[s], B, layout->ctx_len[s], tile_rows, first_block[s],
+                                               num_blocks[s], with_sink);
+        for (int32_t i = 0; i < cnt; ++i, ++n)
+            if (items && n < capacity)
+                items[n] = prefill_item_sel(layout->cu_seqlens[s], layout->sink_len[s], B, layout->ctx_len[s], tile_rows,
+                                            first_block[s], with_sink, i, s);
+    }
+    return n;
+}
+
+int64_t pevlm_query_worklist_window_host(const pevlm_layout *layout, int32_t tile_rows, int32_t num_splits,
+                                         const int32_t *window_blocks, pevlm_work_item *items, int64_t capacity)
+{
+    if (check_layout(layout) != PEVLM_OK) return -1;
+    if (tile_rows < 1 || num_splits < 2 || !window_blocks) {
+        fail(PEVLM_ERR_INVALID_ARG, "tile_rows >= 1, num_splits >= 2 and window_blocks are required");
+        return -1;
+    }
+    Restrict sel;
+    sel.window_blocks = window_blocks;
+    int64_t total_q = total_query_rows(layout);
+    int64_t n = 0;
+    int32_t qrow_base = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        SeqTable tab;
+        fill_table(layout, s, 1, nullptr, &tab, sel);
+        int32_t cnt = query_tiles_of_seq(layout->query_len[s], tile_rows) * num_splits;
+        for (int32_t i = 0; i < cnt; ++i, ++n)
+            if (items && n < capacity)
+                items[n] = query_item_window(layout->cu_seqlens[s], layout->sink_len[s], layout->ctx_len[s],
+                                             layout->query_len[s], tile_rows, num_splits, i, s, qrow_base, (int32_t)total_q,
+                                             kKeyTile, tab.win_start[0]);
         qrow_base += layout->query_len[s];
     }
     return n;

@@ -25,6 +25,14 @@ struct SeqTable {
     int32_t item_base[kMaxSeqsPerLaunch + 1];  // first work item of the sequence (chunk-relative)
     int32_t qrow_base[kMaxSeqsPerLaunch];      // first compact question row of the sequence
     int32_t pos_offset[kMaxSeqsPerLaunch];     // added to every position of the sequence (RoPE)
+    // streaming use: the prefill call may be restricted to context blocks [sel_first, sel_first +
+    // sel_count) (plus the sink rows when sel_sink != 0); the question call may hide the context
+    // before local position win_start (== S: nothing hidden) and then gives the sink its own split
+    int32_t sel_first[kMaxSeqsPerLaunch];
+    int32_t sel_count[kMaxSeqsPerLaunch];
+    int32_t win_start[kMaxSeqsPerLaunch];
+    int32_t sel_sink;
+    int32_t windowed;
 };
 
 struct HeadTable {
@@ -80,6 +88,31 @@ __host__ __device__ inline pevlm_work_item prefill_item(int32_t start, int32_t S
     return it;
 }
 
+// Restriction of the prefill items of a sequence to its sink tiles (if with_sink) and the tiles of
+// context blocks [first, first + count): what a streaming caller computes when new blocks arrive.
+__host__ __device__ inline int32_t prefill_items_of_seq_sel(int32_t S, int32_t B, int32_t C, int32_t tile_rows,
+                                                            int32_t first, int32_t count, int32_t with_sink)
+{
+    int32_t n = with_sink ? ceil_div(S, tile_rows) : 0;
+    if (C > 0 && count > 0) {
+        int32_t nb = ceil_div(C, B);
+        int32_t last = C - (nb - 1) * B;
+        int32_t full = (first + count == nb) ? count - 1 : count;  // selected blocks of B rows
+        n += full * ceil_div(B, tile_rows);
+        if (first + count == nb) n += ceil_div(last, tile_rows);
+    }
+    return n;
+}
+
+__host__ __device__ inline pevlm_work_item prefill_item_sel(int32_t start, int32_t S, int32_t B, int32_t C, int32_t tile_rows,
+                                                            int32_t first, int32_t with_sink, int32_t idx, int32_t seq)
+{
+    int32_t sink_tiles = ceil_div(S, tile_rows);
+    int32_t n_sink_sel = with_sink ? sink_tiles : 0;
+    int32_t full_idx = idx < n_sink_sel ? idx : sink_tiles + first * ceil_div(B, tile_rows) + (idx - n_sink_sel);
+    return prefill_item(start, S, B, C, tile_rows, full_idx, seq);
+}
+
 // Question items (Eq. 5): tiles of question rows x key splits.  The keys of a sequence
 // [start, start + L) are cut into num_splits runs of split_len keys; everything before the
 // question is visible to every question row, keys inside the question are causal.
@@ -120,6 +153,46 @@ __host__ __device__ inline pevlm_work_item query_item(int32_t start, int32_t S, 
     it.diag_start = start + diag_lo;
     it.diag_len = hi - diag_lo;
     it.reserved = split * total_q_rows + qrow_base + r0;  // row of this tile in the partial buffers
+    return it;
+}
+
+// Question items when older context blocks are hidden from the question (sliding window): the
+// visible keys of a tile are the sink [0, S) and [win_start, last key of the tile).  Split 0 is the
+// sink (empty when S == 0); splits 1 .. num_splits-1 cut [win_start, L) into equal runs.
+__host__ __device__ inline pevlm_work_item query_item_window(int32_t start, int32_t S, int32_t C, int32_t Q,
+                                                             int32_t tile_rows, int32_t num_splits, int32_t idx,
+                                                             int32_t seq, int32_t qrow_base, int32_t total_q_rows,
+                                                             int32_t align, int32_t win_start)
+{
+    pevlm_work_item it;
+    int32_t tile = idx / num_splits, split = idx % num_splits;
+    int32_t L = S + C + Q;
+    int32_t r0 = tile * tile_rows;
+    it.seq = seq;
+    it.q_start = start + S + C + r0;
+    it.q_rows = (Q - r0 < tile_rows) ? Q - r0 : tile_rows;
+    it.reserved = split * total_q_rows + qrow_base + r0;
+    int32_t qb = S + C;
+    if (split == 0) {  // the sink: visible to every question row
+        it.full_start = start;
+        it.full_len = S;
+        it.diag_start = start + qb;
+        it.diag_len = 0;
+        return it;
+    }
+    int32_t last_key = qb + r0 + it.q_rows;
+    int32_t sl = split_len_of_seq(L - win_start, num_splits - 1, align);
+    int32_t lo = win_start + (split - 1) * sl, hi = lo + sl;
+    if (hi > last_key) hi = last_key;
+    if (lo > hi) lo = hi;
+    int32_t full_hi = hi < qb ? hi : qb;
+    int32_t full_lo = lo < full_hi ? lo : full_hi;
+    it.full_start = start + full_lo;
+    it.full_len = full_hi - full_lo;
+    int32_t diag_lo = lo > qb ? lo : qb;
+    if (diag_lo > hi) diag_lo = hi;
+    it.diag_start = start + diag_lo;
+    it.diag_len = hi - diag_lo;
     return it;
 }
 

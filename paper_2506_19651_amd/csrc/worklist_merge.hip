@@ -13,8 +13,8 @@ __global__ __launch_bounds__(256) void build_prefill_items_kernel(SeqTable tab, 
     if (i >= total) return;
     int32_t s = 0;
     while (s + 1 < tab.num_seqs && i >= tab.item_base[s + 1]) ++s;
-    items[item_offset + i] = prefill_item(tab.start[s], tab.sink[s], tab.block[s], tab.ctx[s], tile_rows,
-                                          i - tab.item_base[s], tab.seq_index0 + s);
+    items[item_offset + i] = prefill_item_sel(tab.start[s], tab.sink[s], tab.block[s], tab.ctx[s], tile_rows, tab.sel_first[s],
+                                              tab.sel_sink, i - tab.item_base[s], tab.seq_index0 + s);
 }
 
 __global__ __launch_bounds__(256) void build_query_items_kernel(SeqTable tab, int32_t tile_rows, int32_t num_splits,
@@ -27,8 +27,12 @@ __global__ __launch_bounds__(256) void build_query_items_kernel(SeqTable tab, in
     if (i < total) {
         int32_t s = 0;
         while (s + 1 < tab.num_seqs && i >= tab.item_base[s + 1]) ++s;
-        items[item_offset + i] = query_item(tab.start[s], tab.sink[s], tab.ctx[s], tab.query[s], tile_rows, num_splits,
-                                            i - tab.item_base[s], tab.seq_index0 + s, tab.qrow_base[s], total_q_rows, align);
+        items[item_offset + i] =
+            tab.windowed ? query_item_window(tab.start[s], tab.sink[s], tab.ctx[s], tab.query[s], tile_rows, num_splits,
+                                             i - tab.item_base[s], tab.seq_index0 + s, tab.qrow_base[s], total_q_rows, align,
+                                             tab.win_start[s])
+                         : query_item(tab.start[s], tab.sink[s], tab.ctx[s], tab.query[s], tile_rows, num_splits,
+                                      i - tab.item_base[s], tab.seq_index0 + s, tab.qrow_base[s], total_q_rows, align);
     }
     // packed row of every compact question row of this chunk
     int32_t stride = gridDim.x * blockDim.x;

@@ -497,3 +497,104 @@ def test_seeded_sweep_of_small_layouts(oracle, dtype, seed):
         P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base, num_splits=splits)
         torch.cuda.synchronize()
         assert torch.equal(out.view(torch.int16), r["out"].view(torch.int16)), tag
+
+
+# ------------------------------------------------------------------------------------ streaming calls
+STREAM_CASES = [
+    ("bf16_ragged", "bf16", 8, 2, 128, [(300, 392, 1500, 70), (0, 128, 700, 40)]),
+    ("bf16_d64_tiny_blocks", "bf16", 4, 1, 64, [(17, 5, 43, 9)]),
+    ("f32", "f32", 4, 2, 64, [(12, 9, 50, 5), (3, 16, 64, 7)]),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs", STREAM_CASES, ids=[c[0] for c in STREAM_CASES])
+def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(name, dtype, Hq, Hkv, D, seqs):
+    """Sink + first blocks, then the remaining blocks two at a time: every call writes exactly its
+    rows, and the pieces add up to pevlm_block_prefill_attn bit for bit."""
+    w = W.Workload(name, 17, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    ref = torch.full_like(q, float("nan"))
+    P.pevlm_block_prefill_attn(q, k, v, ref, lay, heads)
+    out = torch.full_like(q, float("nan"))
+    nb = [(-(-C // B) if C else 0) for (S, B, C, Q) in seqs]
+    done = [0] * len(seqs)
+    first_call = True
+    while first_call or any(d < n for d, n in zip(done, nb)):
+        count = [min(2, n - d) for d, n in zip(done, nb)]
+        before = out.clone()
+        P.pevlm_block_prefill_attn_blocks(q, k, v, out, lay, heads, done, count, with_sink=first_call)
+        torch.cuda.synchronize()
+        t0 = 0
+        for si, (S, B, C, Q) in enumerate(seqs):
+            sel = torch.zeros(w.total_tokens, dtype=torch.bool, device=DEV)
+            if first_call:
+                sel[t0:t0 + S] = True
+            sel[t0 + S + done[si] * B: min(t0 + S + C, t0 + S + (done[si] + count[si]) * B)] = True
+            rows = slice(t0, t0 + S + C + Q)
+            m = sel[rows]
+            assert torch.equal(out[rows][m].view(torch.int32 if dtype == "f32" else torch.int16),
+                               ref[rows][m].view(torch.int32 if dtype == "f32" else torch.int16))
+            untouched = ~m
+            assert torch.equal(torch.isnan(out[rows][untouched]), torch.isnan(before[rows][untouched]))
+            t0 += S + C + Q
+        done = [d + c for d, c in zip(done, count)]
+        first_call = False
+    both_nan = torch.isnan(out) & torch.isnan(ref)
+    assert torch.equal(torch.nan_to_num(out), torch.nan_to_num(ref)) and torch.equal(torch.isnan(out), both_nan)
+
+
+WINDOW_CASES = [
+    ("bf16_ragged", "bf16", 8, 2, 128, [(300, 392, 1500, 70), (0, 128, 700, 40)], [2, 0], 0),
+    ("bf16_all_and_one", "bf16", 4, 4, 128, [(64, 256, 1024, 130), (200, 100, 950, 33)], [-1, 1], 5),
+    ("bf16_d64", "bf16", 4, 1, 64, [(17, 5, 43, 9)], [3], 2),
+    ("f32", "f32", 4, 2, 64, [(12, 9, 50, 5), (3, 16, 64, 7)], [1, 2], 3),
+    ("f32_window_wider_than_context", "f32", 2, 1, 64, [(5, 8, 24, 6)], [7], 1),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs,windows,splits", WINDOW_CASES, ids=[c[0] for c in WINDOW_CASES])
+def test_windowed_question_against_oracle(oracle, name, dtype, Hq, Hkv, D, seqs, windows, splits):
+    w = W.Workload(name, 18, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((w.total_tokens, Hq), float("nan"), device=DEV)
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    P.pevlm_query_attn_window(q, k, v, out, lay, heads, windows, num_splits=splits, lse=lse)
+    torch.cuda.synchronize()
+    a = w.layout_arrays()
+    olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"], window_blocks=windows)
+    qrows = np.concatenate([np.arange(c0 + S + C, c0 + S + C + Q) for c0, (S, B, C, Q) in zip(a["cu_seqlens"], seqs)])
+    want, want_lse = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=qrows)
+    idx = torch.from_numpy(qrows).to(DEV)
+    got = to_host_f32(out[idx])
+    if dtype == "bf16":
+        check_bf16(got, want, name)
+        assert np.max(np.abs(to_host_f32(lse[idx]) - want_lse)) <= 2e-2
+    else:
+        assert np.max(np.abs(got - want)) <= F32_TOL and np.max(np.abs(to_host_f32(lse[idx]) - want_lse)) <= 1e-4
+    other = torch.ones(w.total_tokens, dtype=torch.bool, device=DEV)
+    other[idx] = False
+    assert torch.isnan(out[other]).all()  # only question rows are written
+
+
+def test_windowed_question_full_size_c3(oracle):
+    """64K-token workload, the question keeps the sink and the 16 newest of its 64 blocks."""
+    w = W.CONFIGS["c3"]
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.full_like(q, float("nan"))
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    P.pevlm_query_attn_window(q, k, v, out, lay, heads, [16])
+    torch.cuda.synchronize()
+    (S, B, C, Q), = w.seqs
+    qrows = np.arange(S + C, S + C + Q, 5)
+    a = w.layout_arrays()
+    olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"], window_blocks=[16])
+    want, _ = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=qrows)
+    check_bf16(to_host_f32(out[torch.from_numpy(qrows).to(DEV)]), want, "c3/window16")

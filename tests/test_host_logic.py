@@ -99,6 +99,85 @@ def test_query_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows, num_spli
         assert np.all(got[lay.cu[si]:lo] == 0)
 
 
+STREAM_LAYOUTS = [
+    [(3, 2, 6, 4)],
+    [(0, 5, 13, 3)],
+    [(300, 392, 1000, 70)],
+    [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)],
+]
+
+
+@pytest.mark.parametrize("seqs", STREAM_LAYOUTS)
+@pytest.mark.parametrize("tile_rows", [1, 16, 128])
+def test_block_range_worklist_is_the_matching_slice_of_the_mask(oracle, seqs, tile_rows):
+    """Items of a block range cover exactly the rows of those blocks (and the sink if asked), each
+    once, with exactly the keys the oracle's mask gives those rows."""
+    lay = P.Layout.from_seqs(seqs)
+    T = lay.total_tokens
+    want = oracle.mask_matrix(oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q))
+    rng = np.random.default_rng(len(seqs) * 100 + tile_rows)
+    for with_sink in (False, True):
+        first, count = [], []
+        for (S, B, C, Q) in seqs:
+            nb = -(-C // B) if C else 0
+            f = int(rng.integers(0, nb + 1))
+            first.append(f)
+            count.append(int(rng.integers(0, nb - f + 1)))
+        items = P.pevlm_prefill_worklist_blocks_host(lay, tile_rows, first, count, with_sink)
+        got, owner = expand_items(items, T) if items else (np.zeros((T, T), np.uint8), np.zeros(T, np.int32))
+        selected = np.zeros(T, bool)
+        for si, (S, B, C, Q) in enumerate(seqs):
+            b0 = lay.cu[si]
+            if with_sink:
+                selected[b0:b0 + S] = True
+            lo = b0 + S + first[si] * B
+            hi = min(b0 + S + C, b0 + S + (first[si] + count[si]) * B)
+            selected[lo:hi] = True
+        assert np.array_equal(owner, selected.astype(np.int32))
+        assert np.array_equal(got[selected], want[selected]) and not got[~selected].any()
+    # the whole range is the plain work list
+    nb_all = [(-(-C // B) if C else 0) for (S, B, C, Q) in seqs]
+    full = P.pevlm_prefill_worklist_blocks_host(lay, tile_rows, [0] * len(seqs), nb_all, True)
+    plain = P.pevlm_prefill_worklist_host(lay, tile_rows)
+    as_rows = lambda its: [[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in its]
+    assert as_rows(full) == as_rows(plain)
+    with pytest.raises(P.PevlmError):
+        P.pevlm_prefill_worklist_blocks_host(lay, tile_rows, [0] * len(seqs), [n + 1 for n in nb_all], True)
+
+
+@pytest.mark.parametrize("seqs", STREAM_LAYOUTS)
+@pytest.mark.parametrize("tile_rows,num_splits", [(16, 2), (16, 5), (128, 3), (1, 2)])
+def test_window_worklist_expands_to_oracle_window_mask(oracle, seqs, tile_rows, num_splits):
+    lay = P.Layout.from_seqs(seqs)
+    T = lay.total_tokens
+    rng = np.random.default_rng(num_splits * 7 + tile_rows)
+    for trial in range(3):
+        windows = []
+        for (S, B, C, Q) in seqs:
+            nb = -(-C // B) if C else 0
+            windows.append(int(rng.integers(-1, nb + 2)))
+        want = oracle.mask_matrix(oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q, window_blocks=windows))
+        items = P.pevlm_query_worklist_window_host(lay, tile_rows, num_splits, windows)
+        got, owner = expand_items_allow_empty(items, T)
+        total_q = sum(q for (_, _, _, q) in seqs)
+        slots = set()
+        for it in items:
+            for r in range(it.q_rows):
+                slot = it.reserved + r
+                assert 0 <= slot < num_splits * total_q and slot not in slots
+                slots.add(slot)
+        assert len(slots) == num_splits * total_q
+        for si, (S, B, C, Q) in enumerate(seqs):
+            lo, hi = lay.cu[si] + S + C, lay.cu[si + 1]
+            assert np.all(owner[lo:hi] == num_splits)
+            assert np.array_equal(got[lo:hi], want[lo:hi])
+            assert np.all(got[lay.cu[si]:lo] == 0)
+
+
+def expand_items_allow_empty(items, T):
+    return expand_items(items, T) if items else (np.zeros((T, T), np.uint8), np.zeros(T, np.int32))
+
+
 def test_visible_pairs_match_oracle_mask_and_golden(oracle):
     for seqs in LAYOUTS:
         lay = P.Layout.from_seqs(seqs)
