@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--no-full-causal", action="store_true")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-rate / copy / cold-cache side measurements")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the widened calls (RoPE folded into attention, streaming, three-axis RoPE): profiler runs "
+                         "use this so that every kernel name stands for one kind of launch")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this path uses no collectives and every GPU box here has one "
@@ -140,7 +143,7 @@ def main():
         "rope_gbs": round(rope_bytes / (ms_rope * 1e-3) / 1e9, 1),
         "query_kv_gbs": round(kv_bytes / (ms_query * 1e-3) / 1e9, 1),
         "roofline": {
-            "kernel": "attn_bf16_kernel<128,false> (block-prefill)",
+            "kernel": "attn_bf16_kernel<128,false,false> (block-prefill)",
             "bound": "mfma",
             "achieved": round(f_prefill / (ms_prefill * 1e-3) / 1e12, 2),
             "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -151,46 +154,47 @@ def main():
         "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
     }
 
-    # the same step with RoPE folded into the attention calls (the prefill call rotates K in place and
-    # fills the cos/sin table; q0 stays un-rotated); outputs are bit-identical to the three-call path
-    ws_pf = torch.empty(P.pevlm_block_prefill_rope_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
-    ws_qf = torch.empty(P.pevlm_query_rope_workspace_bytes(lay, heads, args.num_splits), dtype=torch.uint8, device=dev)
-    out_f = torch.zeros_like(q0)
+    if not args.no_extras:
+        # the same step with RoPE folded into the attention calls (the prefill call rotates K in place and
+        # fills the cos/sin table; q0 stays un-rotated); outputs are bit-identical to the three-call path
+        ws_pf = torch.empty(P.pevlm_block_prefill_rope_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
+        ws_qf = torch.empty(P.pevlm_query_rope_workspace_bytes(lay, heads, args.num_splits), dtype=torch.uint8, device=dev)
+        out_f = torch.zeros_like(q0)
 
-    def step_fused(ev=None):
-        if ev:
-            ev[0].record(stream)
-        if ev:
-            ev[1].record(stream)
-        P.pevlm_block_prefill_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, workspace=ws_pf, stream=stream)
-        if ev:
-            ev[2].record(stream)
-        P.pevlm_query_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, num_splits=args.num_splits, workspace=ws_qf,
-                                stream=stream)
-        if ev:
-            ev[3].record(stream)
+        def step_fused(ev=None):
+            if ev:
+                ev[0].record(stream)
+            if ev:
+                ev[1].record(stream)
+            P.pevlm_block_prefill_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, workspace=ws_pf, stream=stream)
+            if ev:
+                ev[2].record(stream)
+            P.pevlm_query_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, num_splits=args.num_splits, workspace=ws_qf,
+                                    stream=stream)
+            if ev:
+                ev[3].record(stream)
 
-    k.copy_(k0)
-    step_fused()
-    torch.cuda.synchronize()
-    fused_matches = bool(torch.equal(out_f.view(torch.int16), first_out.view(torch.int16)))
-    for _ in range(args.warmup):
+        k.copy_(k0)
         step_fused()
-    events_f = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    tf0 = time.perf_counter()
-    for i in range(args.steps):
-        step_fused(events_f[i])
-    torch.cuda.synchronize()
-    tf1 = time.perf_counter()
-    ms_step_f = (tf1 - tf0) * 1e3 / args.steps
-    result["fused_rope"] = {
-        "ms_per_step": round(ms_step_f, 4),
-        "value": round((f_prefill + f_query) / (ms_step_f * 1e-3) / 1e12, 3),
-        "ms_block_prefill_incl_k_rope": round(float(np.mean([e[1].elapsed_time(e[2]) for e in events_f])), 4),
-        "ms_query_attn": round(float(np.mean([e[2].elapsed_time(e[3]) for e in events_f])), 4),
-        "bit_identical_to_three_call_path": fused_matches,
-    }
+        torch.cuda.synchronize()
+        fused_matches = bool(torch.equal(out_f.view(torch.int16), first_out.view(torch.int16)))
+        for _ in range(args.warmup):
+            step_fused()
+        events_f = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for i in range(args.steps):
+            step_fused(events_f[i])
+        torch.cuda.synchronize()
+        tf1 = time.perf_counter()
+        ms_step_f = (tf1 - tf0) * 1e3 / args.steps
+        result["fused_rope"] = {
+            "ms_per_step": round(ms_step_f, 4),
+            "value": round((f_prefill + f_query) / (ms_step_f * 1e-3) / 1e12, 3),
+            "ms_block_prefill_incl_k_rope": round(float(np.mean([e[1].elapsed_time(e[2]) for e in events_f])), 4),
+            "ms_query_attn": round(float(np.mean([e[2].elapsed_time(e[3]) for e in events_f])), 4),
+            "bit_identical_to_three_call_path": fused_matches,
+        }
 
     if not args.no_probes:
         # what the device sustains: bf16 MFMA issue (two workgroups per CU, as the attention kernel
@@ -240,7 +244,7 @@ def main():
         # streaming calls: one more context block appended to the prompt (rows of the last block only),
         # and the question restricted to the sink plus the newest quarter of the blocks
         nblk = [(-(-c // b) if c else 0) for (_s, b, c, _q) in w.seqs]
-        if min(nblk) >= 4:
+        if min(nblk) >= 4 and not args.no_extras:
             first, one = [n - 1 for n in nblk], [1] * len(nblk)
             ms_blk = timed(lambda: P.pevlm_block_prefill_attn_blocks(q, k, v, out, lay, heads, first, one, False,
                                                                      workspace=ws_p, stream=stream), 10)
@@ -249,14 +253,15 @@ def main():
             ms_win = timed(lambda: P.pevlm_query_attn_window(q, k, v, out, lay, heads, win, workspace=ws_w, stream=stream), 10)
             result["streaming"] = {"ms_prefill_one_appended_block_per_sequence": round(ms_blk, 4),
                                    "ms_query_attn_window_quarter": round(ms_win, 4), "window_blocks": win}
-        # three-axis RoPE on the same tensors (ids of a video prompt with 16x16 / 14x14 tokens per frame)
-        ft, gw = (196, 14) if w.seqs[0][1] % 196 == 0 else (256, 16)
-        ids = torch.from_numpy(W.mrope_position_ids(w, ft, gw)).to(dev)
-        half = w.head_dim // 2
-        sec = (half // 4, (half - half // 4) // 2, half - half // 4 - (half - half // 4) // 2)
-        ms_mr = timed(lambda: P.pevlm_rope_mrope(q, k, T, heads, w.rope_base, ids, sec, stream=stream), 10)
-        result["ms_rope_mrope"] = round(ms_mr, 4)
-        result["rope_mrope_gbs"] = round((rope_bytes + 12 * T) / (ms_mr * 1e-3) / 1e9, 1)
+        if not args.no_extras:
+            # three-axis RoPE on the same tensors (ids of a video prompt with 16x16 / 14x14 tokens per frame)
+            ft, gw = (196, 14) if w.seqs[0][1] % 196 == 0 else (256, 16)
+            ids = torch.from_numpy(W.mrope_position_ids(w, ft, gw)).to(dev)
+            half = w.head_dim // 2
+            sec = (half // 4, (half - half // 4) // 2, half - half // 4 - (half - half // 4) // 2)
+            ms_mr = timed(lambda: P.pevlm_rope_mrope(q, k, T, heads, w.rope_base, ids, sec, stream=stream), 10)
+            result["ms_rope_mrope"] = round(ms_mr, 4)
+            result["rope_mrope_gbs"] = round((rope_bytes + 12 * T) / (ms_mr * 1e-3) / 1e9, 1)
 
     if not args.no_full_causal:
         wf = W.CONFIGS["c3_full_causal"] if args.workload == "c3" else W.small_variant(
