@@ -238,21 +238,15 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 
 // ROPEQ: q holds un-rotated queries; each wavefront rotates its 32 rows once, right after loading
 // them, from the (cos, sin) table of the call (the sequential positions of Sec. "Position Encoding").
+// One work item for one head (or several heads of a KV group, see below): `logical` indexes
+// (KV head group, item, head in group).
 template <int D, bool PARTIAL, bool ROPEQ>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads)
+__device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, int32_t heads_inner, int32_t pack_heads,
+                                          uint8_t *lds_k, uint8_t *lds_v)
 {
     using C = TileCfg<D>;
     constexpr int KT = C::KT, ROWB = C::ROWB, CH = C::CH, NLD = C::NLD, KSTEPS = C::KSTEPS, DBLK = C::DBLK;
     constexpr int VSW = C::VSW, TILEB = C::TILEB, RPI = C::RPI;
-    __shared__ __attribute__((aligned(1024))) uint8_t lds_k[2 * TILEB];
-    __shared__ __attribute__((aligned(1024))) uint8_t lds_v[2 * TILEB];
-
-    // Workgroup -> logical id.  Consecutive workgroup ids land on different XCDs (8 of them, each
-    // with its own L2); give every XCD one contiguous run of logical ids so that the heads of a GQA
-    // group working on the same context block share that XCD's L2.
-    const int32_t per_xcd = gridDim.x >> 3;
-    const int32_t logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= n_logical) return;
     const int32_t inner = logical % heads_inner;
     const int32_t rest = logical / heads_inner;
     // last item first: within a context block the later tiles are the longer ones, and a launch that
@@ -614,6 +608,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t
         }
         if (p.lse && g32 == 0 && row_valid) p.lse[(int64_t)my_row * Hq + h] = (m_ref + __log2f(l_tot)) * 0.69314718056f;
     }
+}
+
+// One workgroup per logical id.  Consecutive workgroup ids land on different XCDs (8 of them, each
+// with its own L2); every XCD gets one contiguous run of logical ids so that the heads of a GQA
+// group working on the same context block share that XCD's L2.
+template <int D, bool PARTIAL, bool ROPEQ>
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_k[2 * TileCfg<D>::TILEB];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_v[2 * TileCfg<D>::TILEB];
+    const int32_t per_xcd = gridDim.x >> 3;
+    const int32_t logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= n_logical) return;
+    attn_item<D, PARTIAL, ROPEQ>(p, logical, heads_inner, pack_heads, lds_k, lds_v);
 }
 
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream)
