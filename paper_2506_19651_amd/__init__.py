@@ -36,4 +36,4 @@ from .binding import (  # noqa: F401
     pevlm_version,
     pevlm_visible_pairs,
 )
-from .cost_model import useful_flops  # noqa: F401
+from .cost_model import choose_block_len, predict_block_prefill_ms, prefill_work, useful_flops  # noqa: F401

@@ -249,3 +249,26 @@ def test_workspace_sizes_cover_items_and_partials():
     for ns in (1, 8, 64):
         need = ns * 128 * 28 * (128 + 2) * 4 + 128 * 4 + ns * ctypes.sizeof(P.WorkItem)
         assert P.pevlm_query_workspace_bytes(lay, heads, ns) >= need
+
+
+def test_time_model_tracks_measured_runs_and_block_length_choice():
+    import workloads as W
+    from paper_2506_19651_amd.cost_model import choose_block_len, predict_block_prefill_ms, prefill_work
+    for line in open(os.path.join(ROOT, "tests", "golden", "measured_block_prefill_ms.txt")):
+        if not line.strip() or line.startswith("#"):
+            continue
+        name, ms = line.split()
+        w = W.CONFIGS[name]
+        lay, heads = P.Layout.from_seqs(w.seqs), P.Heads(w.n_q_heads, w.n_kv_heads, w.head_dim, "bf16")
+        pred = predict_block_prefill_ms(lay, heads)
+        assert abs(pred / float(ms) - 1.0) <= 0.12, (name, pred, ms)
+    # workgroup count of the headline config: 514 items x 28 heads
+    w = W.CONFIGS["c3"]
+    assert prefill_work(P.Layout.from_seqs(w.seqs), P.Heads(28, 4, 128, "bf16"))[0] == 514 * 28
+    # block-length sweep of the 100K-token configuration (2/4/8/16 frames of 196 tokens) under a cap
+    heads = P.Heads(32, 8, 128, "bf16")
+    pick = lambda cap: choose_block_len(392, 100352, 256, heads, [392, 784, 1568, 3136], cap)
+    assert pick(1.0) is None
+    assert pick(1.8)[0] == 784 and pick(2.5)[0] == 1568 and pick(10.0)[0] == 3136
+    assert predict_block_prefill_ms(P.Layout.from_seqs([(392, 392, 100352, 256)]), heads) < \
+        predict_block_prefill_ms(P.Layout.from_seqs([(392, 3136, 100352, 256)]), heads)
