@@ -194,7 +194,7 @@ def test_bf16_no_cross_block_leak_and_reproducible():
     assert np.all((later > 0.0) & (later <= 1.0))
 
 
-FULL = [("c2", 512), ("c3", 384), ("c4a", 256), ("c4d", 256), ("c5b", 256)]
+FULL = [("c2", 512), ("c3", 384), ("c4a", 256), ("c4b", 128), ("c4c", 128), ("c4d", 256), ("c5a", 128), ("c5b", 256)]
 
 
 @pytest.mark.parametrize("name,n_random", FULL, ids=[c[0] for c in FULL])
