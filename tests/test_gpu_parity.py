@@ -598,3 +598,50 @@ def test_windowed_question_full_size_c3(oracle):
     olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"], window_blocks=[16])
     want, _ = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=qrows)
     check_bf16(to_host_f32(out[torch.from_numpy(qrows).to(DEV)]), want, "c3/window16")
+
+
+# ------------------------------------------------------------------------------------ graph capture
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    """The library neither allocates nor synchronises nor clears memory with memset nodes, so the
+    three calls can be recorded into a HIP graph.  Replays (with eager work and synchronisation in
+    between, on fresh inputs each time) must reproduce the eager result bit for bit."""
+    w = W.small_variant(W.CONFIGS["c2"], "graph", [(256, 512, 2048, 64), (0, 128, 500, 20)])
+    lay, heads = layout_heads(w)
+    datas = [W.generate(W.small_variant(w, f"graph{i}", w.seqs, config_id=40 + i)) for i in range(3)]
+    q, k, v = to_device(datas[0]["q"]), to_device(datas[0]["k"]), to_device(datas[0]["v"])
+    out = torch.zeros_like(q)
+    ws_p = torch.empty(P.pevlm_block_prefill_workspace_bytes(lay, heads), dtype=torch.uint8, device=DEV)
+    ws_q = torch.empty(P.pevlm_query_workspace_bytes(lay, heads, 0), dtype=torch.uint8, device=DEV)
+
+    def run():
+        P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+        P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, workspace=ws_p)
+        P.pevlm_query_attn(q, k, v, out, lay, heads, workspace=ws_q)
+
+    # eager references
+    refs = []
+    for d in datas:
+        q.copy_(to_device(d["q"])); k.copy_(to_device(d["k"])); v.copy_(to_device(d["v"]))
+        out.zero_()
+        run()
+        torch.cuda.synchronize()
+        refs.append(out.clone())
+    # capture once (warm-up on a side stream first, as torch asks)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(2):
+        for d, ref in zip(datas, refs):
+            q.copy_(to_device(d["q"])); k.copy_(to_device(d["k"])); v.copy_(to_device(d["v"]))
+            out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), (rep,)
+            (out.float().sum() + 1).item()  # eager work between replays
