@@ -16,7 +16,16 @@
 // Schedule inside a wavefront (software pipeline over key tiles): the value MFMAs of tile t-1 are
 // issued interleaved with the vector-ALU work that turns the scores of tile t into weights, so the
 // matrix cores and the vector ALU of a SIMD overlap within one instruction stream as well as
-// across the two resident wavefronts.
+// across the two resident wavefronts; the wavefront's share of the next K tile and of the current V
+// tile is requested piecewise between those MFMAs.
+//
+// Softmax.  Weights of a tile are formed against the reference maximum the row already has; the
+// row maximum is only computed (and the reference raised, accumulators rescaled) when a lane's sum
+// of weights shows that one of them may have reached 2^8, or on the row's first tile.
+//
+// Variants: PARTIAL writes un-normalised fp32 partials (question attention, merged afterwards);
+// ROPEQ rotates the query rows in registers from a (cos, sin) table instead of expecting rotated
+// queries; items of <= 64 rows are taken for 2 or 4 heads of a KV group by one workgroup.
 #include "bf16_device.h"
 #include "rope_math.h"
 
