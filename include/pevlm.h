@@ -155,6 +155,17 @@ pevlm_status pevlm_query_attn_rope(const void *q, const void *k, const void *v, 
                                    double rope_base, const int32_t *pos_offset, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
+/* The same two calls for three-axis position ids (see pevlm_rope_mrope for pos_ids and section;
+ * pos_ids is DEVICE [3][T] with T = cu_seqlens[num_seqs]).  Workspace sizes are those of the _rope calls. */
+pevlm_status pevlm_block_prefill_attn_mrope(const void *q, void *k, const void *v, void *out, float *lse,
+                                            const pevlm_layout *layout, const pevlm_heads *heads, double rope_base,
+                                            const int32_t *pos_ids, const int32_t *section, int32_t k_is_rotated,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+pevlm_status pevlm_query_attn_mrope(const void *q, const void *k, const void *v, void *out, float *lse,
+                                    const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                                    double rope_base, const int32_t *pos_ids, const int32_t *section, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /*
  * Streaming use (the paper's outlook, Sec. "Conclusion": streaming video, a sliding window that
  * discards the oldest video blocks).  Both calls work on the ordinary packed layout; blocks that

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     load_library,
     pevlm_block_prefill_attn,
     pevlm_block_prefill_attn_blocks,
+    pevlm_block_prefill_attn_mrope,
     pevlm_block_prefill_attn_rope,
     pevlm_block_prefill_rope_workspace_bytes,
     pevlm_block_prefill_workspace_bytes,
@@ -22,6 +23,7 @@ from .binding import (  # noqa: F401
     pevlm_probe_copy,
     pevlm_probe_mfma_bf16,
     pevlm_query_attn,
+    pevlm_query_attn_mrope,
     pevlm_query_attn_rope,
     pevlm_query_attn_window,
     pevlm_query_window_workspace_bytes,

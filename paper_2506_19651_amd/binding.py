@@ -87,6 +87,11 @@ def load_library():
         lib.pevlm_prefill_worklist_blocks_host.argtypes = [LP, i32, i32p, i32p, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_query_worklist_window_host.restype = ctypes.c_int64
         lib.pevlm_query_worklist_window_host.argtypes = [LP, i32, i32, i32p, ctypes.POINTER(WorkItem), ctypes.c_int64]
+        lib.pevlm_block_prefill_attn_mrope.restype = ctypes.c_int
+        lib.pevlm_block_prefill_attn_mrope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, ctypes.c_double, vp, i32p, i32, vp,
+                                                       ctypes.c_size_t, vp]
+        lib.pevlm_query_attn_mrope.restype = ctypes.c_int
+        lib.pevlm_query_attn_mrope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, ctypes.c_double, vp, i32p, vp, ctypes.c_size_t, vp]
         lib.pevlm_last_error.restype = ctypes.c_char_p
         lib.pevlm_version.restype = i32
         lib.pevlm_prefill_tile_rows.restype = i32
@@ -244,6 +249,27 @@ def pevlm_query_attn_rope(q, k, v, out, layout: Layout, heads: Heads, rope_base:
     _check(load_library().pevlm_query_attn_rope(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(), heads.ref(),
                                                 int(num_splits), float(rope_base), offp, _ptr(workspace),
                                                 workspace.numel(), _stream_ptr(stream)))
+
+
+def pevlm_block_prefill_attn_mrope(q, k, v, out, layout: Layout, heads: Heads, rope_base: float, pos_ids, section,
+                                   k_is_rotated: bool = False, lse=None, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_block_prefill_rope_workspace_bytes(layout, heads), q)
+    _s, sp = _i32_array(section)
+    _check(load_library().pevlm_block_prefill_attn_mrope(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
+                                                         heads.ref(), float(rope_base), _ptr(pos_ids), sp,
+                                                         int(bool(k_is_rotated)), _ptr(workspace), workspace.numel(),
+                                                         _stream_ptr(stream)))
+
+
+def pevlm_query_attn_mrope(q, k, v, out, layout: Layout, heads: Heads, rope_base: float, pos_ids, section, num_splits: int = 0,
+                           lse=None, workspace=None, stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_query_rope_workspace_bytes(layout, heads, num_splits), q)
+    _s, sp = _i32_array(section)
+    _check(load_library().pevlm_query_attn_mrope(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(), heads.ref(),
+                                                 int(num_splits), float(rope_base), _ptr(pos_ids), sp, _ptr(workspace),
+                                                 workspace.numel(), _stream_ptr(stream)))
 
 
 def pevlm_rope_mrope(q, k, num_tokens: int, heads: Heads, rope_base: float, pos_ids, section, stream=None):

@@ -92,6 +92,24 @@ struct Restrict {
     const int32_t *window_blocks = nullptr;                       // question: last W blocks visible (<0: all)
 };
 
+// Three-axis position ids for the calls with RoPE folded in (pos_ids == NULL: sequential positions).
+struct Axes {
+    const int32_t *pos_ids = nullptr;  // DEVICE [3][T]
+    int32_t sec0 = 0, sec01 = 0;       // sections [0, sec0), [sec0, sec01), [sec01, D/2)
+};
+
+static pevlm_status check_axes(const pevlm_heads *heads, const int32_t *pos_ids, const int32_t *section, Axes *ax)
+{
+    if (!pos_ids || ((uintptr_t)pos_ids & 3)) return fail(PEVLM_ERR_INVALID_ARG, "pos_ids must be a 4-byte aligned device pointer");
+    if (!section || section[0] < 0 || section[1] < 0 || section[2] < 0 ||
+        (int64_t)section[0] + section[1] + section[2] != heads->head_dim / 2)
+        return fail(PEVLM_ERR_INVALID_ARG, "section must hold three non-negative counts that add up to head_dim/2");
+    ax->pos_ids = pos_ids;
+    ax->sec0 = section[0];
+    ax->sec01 = section[0] + section[1];
+    return PEVLM_OK;
+}
+
 static int32_t blocks_of(const pevlm_layout *lay, int32_t s)
 {
     return lay->ctx_len[s] > 0 ? (lay->ctx_len[s] + lay->block_len[s] - 1) / lay->block_len[s] : 0;
@@ -288,7 +306,7 @@ pevlm_status pevlm_rope_mrope(void *q, void *k, int64_t num_tokens, const pevlm_
     if (!pos_ids || ((uintptr_t)pos_ids & 3)) return fail(PEVLM_ERR_INVALID_ARG, "pos_ids must be a 4-byte aligned device pointer");
     hipError_t e = launch_rope_mrope(q, k, num_tokens, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
                                      heads->dtype == PEVLM_BF16, rope_base, pos_ids, section[0], section[0] + section[1],
-                                     (hipStream_t)stream);
+                                     nullptr, (hipStream_t)stream);
     return e == hipSuccess ? PEVLM_OK : hip_fail(e, "mrope launch");
 }
 
@@ -313,7 +331,8 @@ size_t pevlm_block_prefill_rope_workspace_bytes(const pevlm_layout *layout, cons
 static pevlm_status prefill_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                                  const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
                                  size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
-                                 const int32_t *pos_offset, bool rotate_k, const Restrict &sel = Restrict())
+                                 const int32_t *pos_offset, bool rotate_k, const Restrict &sel = Restrict(),
+                                 const Axes &ax = Axes())
 {
     pevlm_status st = check_layout(layout);
     if (st != PEVLM_OK) return st;
@@ -332,8 +351,13 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
     int32_t tile_rows = tile_rows_of(heads, false);
     int64_t n_items = count_prefill_items(layout, tile_rows, sel);
     if (n_items == 0) {  // no sink or context rows: nothing to attend, but the keys are still rotated if asked
-        if (fuse_rope && rotate_k && layout->cu_seqlens[layout->num_seqs] > 0)
-            return pevlm_rope_seq(nullptr, const_cast<void *>(k), layout, heads, rope_base, pos_offset, stream);
+        if (fuse_rope && rotate_k && layout->cu_seqlens[layout->num_seqs] > 0) {
+            if (!ax.pos_ids) return pevlm_rope_seq(nullptr, const_cast<void *>(k), layout, heads, rope_base, pos_offset, stream);
+            hipError_t e = launch_rope_mrope(nullptr, const_cast<void *>(k), layout->cu_seqlens[layout->num_seqs], heads->n_q_heads,
+                                             heads->n_kv_heads, heads->head_dim, true, rope_base, ax.pos_ids, ax.sec0, ax.sec01,
+                                             nullptr, (hipStream_t)stream);
+            return e == hipSuccess ? PEVLM_OK : hip_fail(e, "mrope launch");
+        }
         return PEVLM_OK;
     }
     if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
@@ -344,6 +368,12 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
     hipStream_t hs = (hipStream_t)stream;
     pevlm_work_item *items = (pevlm_work_item *)workspace;
     float *rope_tab = (float *)((char *)workspace + align256((size_t)n_items * sizeof(pevlm_work_item)));
+    const int64_t T = layout->cu_seqlens[layout->num_seqs];
+    if (fuse_rope && ax.pos_ids && rotate_k) {  // three-axis ids: one launch rotates K of all tokens and fills the table
+        hipError_t e = launch_rope_mrope(nullptr, const_cast<void *>(k), T, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
+                                         true, rope_base, ax.pos_ids, ax.sec0, ax.sec01, rope_tab, hs);
+        if (e != hipSuccess) return hip_fail(e, "mrope launch");
+    }
     int32_t offset = 0;
     for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
         SeqTable tab;
@@ -356,11 +386,12 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
             hipError_t e = launch_build_prefill_items(tab, tile_rows, items, offset, hs);
             if (e != hipSuccess) return hip_fail(e, "work-list builder launch");
         }
-        if (fuse_rope) {  // table entries = packed rows of this chunk's sequences
+        if (fuse_rope && !(ax.pos_ids && rotate_k)) {  // table entries = packed rows of this chunk's sequences
             hipError_t e = rotate_k ? launch_rope(nullptr, const_cast<void *>(k), tab, heads->n_q_heads, heads->n_kv_heads,
                                                   heads->head_dim, true, rope_base, rope_tab, hs)
                                     : launch_rope_table(rope_tab, nullptr, tab, heads->head_dim, rope_base,
-                                                        layout->cu_seqlens[s0], layout->cu_seqlens[s0 + n], hs);
+                                                        layout->cu_seqlens[s0], layout->cu_seqlens[s0 + n], ax.pos_ids, T,
+                                                        ax.sec0, ax.sec01, hs);
             if (e != hipSuccess) return hip_fail(e, "rope table launch");
         }
         offset += tab.item_base[n];
@@ -425,7 +456,7 @@ size_t pevlm_query_rope_workspace_bytes(const pevlm_layout *layout, const pevlm_
 static pevlm_status query_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                                const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
                                void *workspace, size_t workspace_bytes, void *stream, bool fuse_rope, double rope_base,
-                               const int32_t *pos_offset, const Restrict &sel = Restrict())
+                               const int32_t *pos_offset, const Restrict &sel = Restrict(), const Axes &ax = Axes())
 {
     pevlm_status st = check_layout(layout);
     if (st != PEVLM_OK) return st;
@@ -470,7 +501,8 @@ static pevlm_status query_impl(const void *q, const void *k, const void *v, void
                                                     kKeyTile, items, item_offset, qrow, hs);
             if (e != hipSuccess) return hip_fail(e, "query work-list builder launch");
             if (fuse_rope) {  // table entries = compact question rows of this chunk (mapped through qrow)
-                e = launch_rope_table(rope_tab, qrow, tab, heads->head_dim, rope_base, entry_begin, qrow_base, hs);
+                e = launch_rope_table(rope_tab, qrow, tab, heads->head_dim, rope_base, entry_begin, qrow_base, ax.pos_ids,
+                                      layout->cu_seqlens[layout->num_seqs], ax.sec0, ax.sec01, hs);
                 if (e != hipSuccess) return hip_fail(e, "rope table launch");
             }
         }
@@ -507,6 +539,34 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
                               void *workspace, size_t workspace_bytes, void *stream)
 {
     return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, false, 0.0, nullptr);
+}
+
+pevlm_status pevlm_block_prefill_attn_mrope(const void *q, void *k, const void *v, void *out, float *lse,
+                                            const pevlm_layout *layout, const pevlm_heads *heads, double rope_base,
+                                            const int32_t *pos_ids, const int32_t *section, int32_t k_is_rotated,
+                                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    pevlm_status st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    Axes ax;
+    st = check_axes(heads, pos_ids, section, &ax);
+    if (st != PEVLM_OK) return st;
+    return prefill_impl(q, k, v, out, lse, layout, heads, workspace, workspace_bytes, stream, true, rope_base, nullptr,
+                        k_is_rotated == 0, Restrict(), ax);
+}
+
+pevlm_status pevlm_query_attn_mrope(const void *q, const void *k, const void *v, void *out, float *lse,
+                                    const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits, double rope_base,
+                                    const int32_t *pos_ids, const int32_t *section, void *workspace, size_t workspace_bytes,
+                                    void *stream)
+{
+    pevlm_status st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    Axes ax;
+    st = check_axes(heads, pos_ids, section, &ax);
+    if (st != PEVLM_OK) return st;
+    return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, true, rope_base, nullptr,
+                      Restrict(), ax);
 }
 
 size_t pevlm_query_window_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)

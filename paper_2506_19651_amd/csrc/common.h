@@ -238,10 +238,12 @@ hipError_t launch_build_query_items(const SeqTable &tab, int32_t tile_rows, int3
 // table != NULL (bf16 only): also stores (cos, sin) [packed row][D/2] for the fused query rotation
 hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_t Hkv, int32_t D, bool bf16,
                        double rope_base, float *table, hipStream_t stream);
+// pos3 != NULL: three-axis ids [3][T] (device) with sections [0, sec0), [sec0, sec01), [sec01, D/2)
 hipError_t launch_rope_table(float *table, const int32_t *row_of_entry, const SeqTable &tab, int32_t D, double rope_base,
-                             int32_t entry_begin, int32_t entry_end, hipStream_t stream);
+                             int32_t entry_begin, int32_t entry_end, const int32_t *pos3, int64_t T, int32_t sec0, int32_t sec01,
+                             hipStream_t stream);
 hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
-                             const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream);
+                             const int32_t *pos3, int32_t sec0, int32_t sec01, float *table, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);  // p.rope_tab selects the fused variant
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);

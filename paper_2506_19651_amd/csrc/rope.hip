@@ -124,36 +124,46 @@ __global__ __launch_bounds__(256) void rope_kernel(void *q, void *k, SeqTable ta
 // bits pevlm_rope_seq would have stored.  One thread per (entry, 8 pair indices).
 template <int D>
 __global__ __launch_bounds__(256) void rope_table_kernel(float2 *table, const int32_t *row_of_entry, SeqTable tab, RopeFreq fr,
-                                                         int32_t entry_begin, int32_t entry_end)
+                                                         int32_t entry_begin, int32_t entry_end, const int32_t *pos3, int64_t T,
+                                                         int32_t sec0, int32_t sec01)
 {
     constexpr int LANES_PER_ENTRY = D / 16;
     const int32_t e = entry_begin + (blockIdx.x * 256 + threadIdx.x) / LANES_PER_ENTRY;
     if (e >= entry_end) return;
     const int32_t i0 = (threadIdx.x % LANES_PER_ENTRY) * 8;
     const int32_t row = row_of_entry ? row_of_entry[e] : e;
-    int32_t s = 0;
-    while (s + 1 < tab.num_seqs && row >= tab.start[s + 1]) ++s;
-    const double pos = (double)(row - tab.start[s] + tab.pos_offset[s]);
+    double pos_axis[3];
+    if (pos3) {  // three position axes: pair index i takes the id of the axis whose section holds it
+#pragma unroll
+        for (int a = 0; a < 3; ++a) pos_axis[a] = (double)pos3[(int64_t)a * T + row];
+    } else {
+        int32_t s = 0;
+        while (s + 1 < tab.num_seqs && row >= tab.start[s + 1]) ++s;
+        pos_axis[0] = pos_axis[1] = pos_axis[2] = (double)(row - tab.start[s] + tab.pos_offset[s]);
+        sec0 = sec01 = D;  // every pair index on axis 0
+    }
     float2 *dst = table + (int64_t)e * (D / 2) + i0;
 #pragma unroll
     for (int j = 0; j < 8; j += 2) {
         float c0, s0, c1, s1;
-        rope_cos_sin<false>(pos, fr.inv_freq[i0 + j], c0, s0);
-        rope_cos_sin<false>(pos, fr.inv_freq[i0 + j + 1], c1, s1);
+        const int32_t ia = i0 + j, ib = i0 + j + 1;
+        rope_cos_sin<false>(ia < sec0 ? pos_axis[0] : (ia < sec01 ? pos_axis[1] : pos_axis[2]), fr.inv_freq[ia], c0, s0);
+        rope_cos_sin<false>(ib < sec0 ? pos_axis[0] : (ib < sec01 ? pos_axis[1] : pos_axis[2]), fr.inv_freq[ib], c1, s1);
         *reinterpret_cast<float4 *>(dst + j) = make_float4(c0, s0, c1, s1);
     }
 }
 
 hipError_t launch_rope_table(float *table, const int32_t *row_of_entry, const SeqTable &tab, int32_t D, double rope_base,
-                             int32_t entry_begin, int32_t entry_end, hipStream_t stream)
+                             int32_t entry_begin, int32_t entry_end, const int32_t *pos3, int64_t T, int32_t sec0, int32_t sec01,
+                             hipStream_t stream)
 {
     if (entry_end <= entry_begin) return hipSuccess;
     RopeFreq fr;
     for (int i = 0; i < 64; ++i) fr.inv_freq[i] = i < D / 2 ? pow(rope_base, -2.0 * (double)i / (double)D) : 0.0;
     const int32_t per_block = 256 / (D / 16);
     dim3 grid((entry_end - entry_begin + per_block - 1) / per_block);
-    if (D == 128) hipLaunchKernelGGL((rope_table_kernel<128>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end);
-    else hipLaunchKernelGGL((rope_table_kernel<64>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end);
+    if (D == 128) hipLaunchKernelGGL((rope_table_kernel<128>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end, pos3, T, sec0, sec01);
+    else hipLaunchKernelGGL((rope_table_kernel<64>), grid, dim3(256), 0, stream, (float2 *)table, row_of_entry, tab, fr, entry_begin, entry_end, pos3, T, sec0, sec01);
     return hipGetLastError();
 }
 
@@ -192,10 +202,10 @@ hipError_t launch_rope(void *q, void *k, const SeqTable &tab, int32_t Hq, int32_
 }
 
 hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
-                             const int32_t *pos3, int32_t sec0, int32_t sec01, hipStream_t stream)
+                             const int32_t *pos3, int32_t sec0, int32_t sec01, float *table, hipStream_t stream)
 {
     SeqTable tab = {};
-    return launch_rope_any<true>(q, k, tab, Hq, Hkv, D, bf16, rope_base, 0, (int32_t)T, pos3, T, sec0, sec01, nullptr, stream);
+    return launch_rope_any<true>(q, k, tab, Hq, Hkv, D, bf16, rope_base, 0, (int32_t)T, pos3, T, sec0, sec01, table, stream);
 }
 
 }  // namespace pevlm

@@ -645,3 +645,35 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
             torch.cuda.synchronize()
             assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), (rep,)
             (out.float().sum() + 1).item()  # eager work between replays
+
+
+@pytest.mark.parametrize("k_is_rotated", [False, True])
+def test_folded_rope_with_three_axis_ids_equals_three_call_path_bitwise(oracle, k_is_rotated):
+    w = W.Workload("mrope_fused", 19, "bf16", 8, 2, 128, 1.0e6, [(300, 512, 1536, 70), (256, 256, 900, 33)], 0.5)
+    data = W.generate(w)
+    ids = W.mrope_position_ids(w, 256, 16)
+    section = (16, 24, 24)
+    lay, heads = layout_heads(w)
+    ids_d = torch.from_numpy(ids).to(DEV)
+    # three calls
+    q1, k1, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    ref = torch.full_like(q1, float("nan"))
+    P.pevlm_rope_mrope(q1, k1, w.total_tokens, heads, w.rope_base, ids_d, section)
+    P.pevlm_block_prefill_attn(q1, k1, v, ref, lay, heads)
+    P.pevlm_query_attn(q1, k1, v, ref, lay, heads, num_splits=3)
+    # folded
+    q2, k2 = to_device(data["q"]), to_device(data["k"])
+    if k_is_rotated:
+        P.pevlm_rope_mrope(None, k2, w.total_tokens, heads, w.rope_base, ids_d, section)
+    out = torch.full_like(q2, float("nan"))
+    P.pevlm_block_prefill_attn_mrope(q2, k2, v, out, lay, heads, w.rope_base, ids_d, section, k_is_rotated=k_is_rotated)
+    P.pevlm_query_attn_mrope(q2, k2, v, out, lay, heads, w.rope_base, ids_d, section, num_splits=3)
+    torch.cuda.synchronize()
+    assert torch.equal(k2.view(torch.int16), k1.view(torch.int16))
+    assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+    assert torch.equal(q2.view(torch.int16), to_device(data["q"]).view(torch.int16))
+    # and against the oracle
+    q_exact = oracle.rope_mrope(data["q"], ids, section, w.rope_base)
+    k_exact = oracle.rope_mrope(data["k"], ids, section, w.rope_base)
+    want, _ = oracle.attn(q_exact, k_exact, data["v"], oracle_layout(oracle, w))
+    check_bf16(to_host_f32(out), want, "mrope_fused")
