@@ -33,6 +33,12 @@ MUTATIONS = [
     ("mrope_section_boundary", "int axis = i < section[0] ? 0 :", "int axis = i <= section[0] ? 0 :"),
     ("mrope_axes_swapped", "(i < section[0] + section[1] ? 1 : 2);", "(i < section[0] + section[1] ? 2 : 1);"),
     ("mrope_sign", "o[i] = lo * ca - hi * sa;", "o[i] = lo * ca + hi * sa;"),
+    ("position_offset_dropped", "pos[t] = (int32_t)(t - lay->cu_seqlens[s]) + (pos_offset ? pos_offset[s] : 0);",
+     "pos[t] = (int32_t)(t - lay->cu_seqlens[s]);"),
+    ("position_offset_of_sequence_0_for_all", "pos[t] = (int32_t)(t - lay->cu_seqlens[s]) + (pos_offset ? pos_offset[s] : 0);",
+     "pos[t] = (int32_t)(t - lay->cu_seqlens[s]) + (pos_offset ? pos_offset[0] : 0);"),
+    ("custom_scale_doubled", "softmax_scale > 0.0 ? dot * softmax_scale :", "softmax_scale > 0.0 ? dot * softmax_scale * 2.0 :"),
+    ("custom_scale_ignored", "softmax_scale > 0.0 ? dot * softmax_scale :", "softmax_scale > 1e300 ? dot * softmax_scale :"),
     ("mrope_frequency_restarts_per_section", "double angle = p_axis * pow(rope_base, -(2.0 * i) / D);",
      "double angle = p_axis * pow(rope_base, -(2.0 * (i - (axis == 0 ? 0 : axis == 1 ? section[0] : section[0] + section[1]))) / D);"),
 ]

@@ -336,6 +336,101 @@ def test_p7_constant_position_offset_changes_nothing(oracle):
     assert np.max(np.abs(a - b)) <= 1e-9
 
 
+def test_p7_position_offsets_written_out(oracle):
+    """Sequential positions with a per-sequence start: token n of sequence s sits at o_s + n
+    (Sec. "Position Encoding": the ids of the whole prompt are kept), spelt out by hand."""
+    seqs = [(2, 2, 3, 1), (1, 3, 3, 0), (0, 1, 0, 2)]
+    lay = make_layout(oracle, seqs)
+    assert oracle.positions(lay).tolist() == [0, 1, 2, 3, 4, 5, 0, 1, 2, 3, 0, 1]
+    assert oracle.positions(lay, [100, 7, 50000]).tolist() == [100, 101, 102, 103, 104, 105, 7, 8, 9, 10, 50000, 50001]
+    # offsets of distinct sequences are independent of each other
+    assert oracle.positions(lay, [0, 9, 0]).tolist() == [0, 1, 2, 3, 4, 5, 9, 10, 11, 12, 0, 1]
+
+
+def test_p7_rotation_under_position_offsets_matches_complex_multiplication(oracle):
+    """The whole path with non-zero starts: rotated Q/K equal the complex-multiplication brute force
+    at positions o_s + n, and the attention output equals the brute force evaluated at those
+    positions.  Distinct per-sequence offsets; the path is not invariant to a dropped or shared
+    offset in its rotated tensors even though attention outputs are (relative property)."""
+    seqs = [(3, 4, 9, 2), (2, 3, 5, 3)]
+    offs = [37, 1201]
+    Hq, Hkv, D, base = 2, 1, 8, 1.0e4
+    lay = make_layout(oracle, seqs)
+    T = lay.total_tokens
+    q, k, v = rand_qkv(T, Hq, Hkv, D)
+    want_pos = np.concatenate([np.arange(3 + 9 + 2) + 37, np.arange(2 + 5 + 3) + 1201]).astype(np.float64)
+    pos = oracle.positions(lay, offs)
+    np.testing.assert_array_equal(pos, want_pos.astype(np.int32))
+    np.testing.assert_allclose(oracle.rope(k, pos, base), brute_rope_complex(k, want_pos, base), atol=1e-11, rtol=0)
+    np.testing.assert_allclose(oracle.rope(q, pos, base, rows=[1, 15, 20]),
+                               brute_rope_complex(q, want_pos, base)[[1, 15, 20]], atol=1e-11, rtol=0)
+    # rotated keys under an offset differ from the ones without (the offset really enters the angle)
+    assert np.max(np.abs(oracle.rope(k, pos, base) - oracle.rope(k, oracle.positions(lay), base))) > 0.1
+
+
+# ------------------------------------------------------------------ caller-chosen softmax scale (Eq. 1)
+def brute_scaled_attention(q_rows, k_rows, v_rows, visible, scale):
+    """Plain loops: softmax(scale * q.k over the visible keys) V, for each query row r and its key set
+    visible[r] (indices into k_rows)."""
+    out, lse = [], []
+    for r, keys in enumerate(visible):
+        scores = [scale * sum(q_rows[r][d] * k_rows[j][d] for d in range(len(q_rows[r]))) for j in keys]
+        mx = max(scores)
+        ws = [math.exp(s - mx) for s in scores]
+        tot = sum(ws)
+        out.append([sum(w * v_rows[j][d] for w, j in zip(ws, keys)) / tot for d in range(len(v_rows[0]))])
+        lse.append(mx + math.log(tot))
+    return out, lse
+
+
+@pytest.mark.parametrize("scale", [0.05, 0.2, 1.7])
+def test_p13_custom_softmax_scale_against_brute_force(oracle, scale):
+    """Eq. 1 with the caller's factor in place of 1/sqrt(d): out and lse against plain loops over the
+    visible keys of each row (visibility written out from Eq. 3-5, not taken from the oracle)."""
+    (S, B, C, Q) = (3, 4, 10, 3)
+    L = S + C + Q
+    Hq, Hkv, D, base = 2, 1, 6, 1.0e4
+    lay = make_layout(oracle, [(S, B, C, Q)])
+    q, k, v = rand_qkv(L, Hq, Hkv, D)
+    posf = np.arange(L, dtype=np.float64)
+    qr, kr = brute_rope_complex(q, posf, base), brute_rope_complex(k, posf, base)
+    visible = []
+    for i in range(L):
+        if i < S or i >= S + C:
+            visible.append(list(range(i + 1)))
+        else:
+            b0 = S + ((i - S) // B) * B
+            visible.append(list(range(S)) + list(range(b0, i + 1)))
+    got, got_lse = oracle.forward(q, k, v, lay, base, softmax_scale=scale)
+    for h in range(Hq):
+        want, want_lse = brute_scaled_attention(qr[:, h].tolist(), kr[:, 0].tolist(), v[:, 0].tolist(), visible, scale)
+        assert np.max(np.abs(got[:, h] - np.asarray(want))) <= 1e-12
+        assert np.max(np.abs(got_lse[:, h] - np.asarray(want_lse))) <= 1e-12
+
+
+def test_p13_explicit_default_scale_and_scale_sensitivity(oracle):
+    """Passing 1/sqrt(D) explicitly is the default (same arithmetic up to one rounding of the factor);
+    another factor gives another answer; a huge factor tends to the hard maximum (one-hot weights)."""
+    (S, B, C, Q) = (4, 5, 10, 2)
+    L = S + C + Q
+    Hq, Hkv, D, base = 2, 2, 16, 1.0e4
+    lay = make_layout(oracle, [(S, B, C, Q)])
+    q, k, v = rand_qkv(L, Hq, Hkv, D)
+    a, la = oracle.forward(q, k, v, lay, base)
+    b, lb = oracle.forward(q, k, v, lay, base, softmax_scale=1.0 / math.sqrt(D))
+    assert np.max(np.abs(a - b)) <= 1e-14 and np.max(np.abs(la - lb)) <= 1e-14
+    c, _ = oracle.forward(q, k, v, lay, base, softmax_scale=2.0 / math.sqrt(D))
+    assert np.max(np.abs(a - c)) > 1e-3
+    # scale -> large: every row returns the value of its best visible key
+    posf = np.arange(L, dtype=np.float64)
+    qr, kr = brute_rope_complex(q, posf, base), brute_rope_complex(k, posf, base)
+    hard, _ = oracle.forward(q, k, v, lay, base, softmax_scale=1.0e4)
+    i = L - 1  # a question row: all keys visible
+    for h in range(Hq):
+        best = int(np.argmax(kr[:, h] @ qr[i, h]))
+        np.testing.assert_allclose(hard[i, h], v[best, h], atol=1e-9)
+
+
 # ------------------------------------------------------------------ multimodal RoPE (three axes)
 def brute_mrope_complex(x, pos3, section, base):
     """Independent evaluation: pair (i, i+D/2) as one complex number, turned by exp(j * angle), the
