@@ -70,7 +70,11 @@ def main():
     lay = P.Layout.from_seqs(w.seqs)
     heads = P.Heads(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     q0, k0, v = to_dev(data["q"]), to_dev(data["k"]), to_dev(data["v"])
+    # q, k: rotated once (what the attention calls of every step read); qs, ks: the tensors the timed
+    # RoPE call rotates in place step after step (its time does not depend on the values)
     q, k = q0.clone(), k0.clone()
+    qs, ks = q0.clone(), k0.clone()
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
     out = torch.zeros_like(q)
     ws_p = torch.empty(P.pevlm_block_prefill_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
     ws_q = torch.empty(P.pevlm_query_workspace_bytes(lay, heads, args.num_splits), dtype=torch.uint8, device=dev)
@@ -79,7 +83,7 @@ def main():
     def step(ev=None):
         if ev:
             ev[0].record(stream)
-        P.pevlm_rope_seq(q, k, lay, heads, w.rope_base, stream=stream)
+        P.pevlm_rope_seq(qs, ks, lay, heads, w.rope_base, stream=stream)
         if ev:
             ev[1].record(stream)
         P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, workspace=ws_p, stream=stream)
@@ -89,7 +93,8 @@ def main():
         if ev:
             ev[3].record(stream)
 
-    # first pass on the pristine inputs: kept for the accuracy figures reported next to the timing
+    # first pass: kept for the accuracy figures reported next to the timing (every later pass
+    # computes the same output from the same once-rotated q, k)
     step()
     torch.cuda.synchronize()
     first_out = out.clone()
@@ -166,15 +171,15 @@ def main():
                 ev[0].record(stream)
             if ev:
                 ev[1].record(stream)
-            P.pevlm_block_prefill_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, workspace=ws_pf, stream=stream)
+            P.pevlm_block_prefill_attn_rope(q0, kf, v, out_f, lay, heads, w.rope_base, workspace=ws_pf, stream=stream)
             if ev:
                 ev[2].record(stream)
-            P.pevlm_query_attn_rope(q0, k, v, out_f, lay, heads, w.rope_base, num_splits=args.num_splits, workspace=ws_qf,
+            P.pevlm_query_attn_rope(q0, kf, v, out_f, lay, heads, w.rope_base, num_splits=args.num_splits, workspace=ws_qf,
                                     stream=stream)
             if ev:
                 ev[3].record(stream)
 
-        k.copy_(k0)
+        kf = k0.clone()  # rotated in place by every fused step (timing only; the first pass is the checked one)
         step_fused()
         torch.cuda.synchronize()
         fused_matches = bool(torch.equal(out_f.view(torch.int16), first_out.view(torch.int16)))
@@ -259,7 +264,7 @@ def main():
             ids = torch.from_numpy(W.mrope_position_ids(w, ft, gw)).to(dev)
             half = w.head_dim // 2
             sec = (half // 4, (half - half // 4) // 2, half - half // 4 - (half - half // 4) // 2)
-            ms_mr = timed(lambda: P.pevlm_rope_mrope(q, k, T, heads, w.rope_base, ids, sec, stream=stream), 10)
+            ms_mr = timed(lambda: P.pevlm_rope_mrope(qs, ks, T, heads, w.rope_base, ids, sec, stream=stream), 10)
             result["ms_rope_mrope"] = round(ms_mr, 4)
             result["rope_mrope_gbs"] = round((rope_bytes + 12 * T) / (ms_mr * 1e-3) / 1e9, 1)
 

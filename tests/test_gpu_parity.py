@@ -216,6 +216,90 @@ def test_bf16_full_size_sampled_rows(oracle, name, n_random):
     assert float(out.float().abs().max()) <= vmax * 1.01
 
 
+def test_bf16_full_causal_c3_sampled_rows(oracle):
+    """The dense causal layout bench.py times as the comparison (one 65 920-row block, no sink, up to
+    1030 key tiles per work item): first and last rows, both sides of 128-row tile edges spread over
+    the sequence, and seeded random rows against the oracle."""
+    w = W.CONFIGS["c3_full_causal"]
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    out = torch.full_like(q, float("nan"))
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    P.pevlm_block_prefill_attn(q, k, v, out, lay, heads)
+    torch.cuda.synchronize()
+    T = w.total_tokens
+    edges = [128 * e for e in (1, 2, 3, 17, 100, 255, 256, 400, 511, 514)]
+    rows = [0, 1, 2, 63, 64, T - 2, T - 1] + [e - 1 for e in edges] + edges
+    rows += [int(x) for x in np.random.default_rng(3).integers(0, T, 130)]
+    rows = np.unique(np.asarray(rows, dtype=np.int64))
+    want, _ = oracle_rows(oracle, w, data, rows)
+    check_bf16(to_host_f32(out[torch.from_numpy(rows).to(DEV)]), want, "c3_full_causal")
+    assert torch.isfinite(out.float()).all()
+
+
+SCALE_CASES = [
+    ("f32_d64", "f32", 4, 2, 64, [(12, 9, 50, 5), (3, 16, 64, 7)], 0.05, 3),
+    ("f32_d128", "f32", 2, 1, 128, [(40, 33, 150, 21)], 0.2, 2),
+    ("bf16_d128", "bf16", 8, 2, 128, [(300, 392, 1000, 70)], 0.05, 4),
+    ("bf16_d128_sharp", "bf16", 4, 2, 128, [(130, 200, 777, 129), (0, 64, 320, 5)], 0.2, 0),
+    ("bf16_d64", "bf16", 4, 1, 64, [(100, 160, 500, 33)], 0.2, 3),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs,scale,splits", SCALE_CASES, ids=[c[0] for c in SCALE_CASES])
+def test_caller_chosen_softmax_scale(oracle, name, dtype, Hq, Hkv, D, seqs, scale, splits):
+    """Eq. 1 with the caller's factor in place of 1/sqrt(d): all three calls (and the pair with RoPE
+    folded in), out and lse, against the oracle evaluated with the same factor; and the result
+    differs from the default-scale one (the factor really is used)."""
+    w = W.Workload("scale_" + name, 21, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
+    data = W.generate(w)
+    r = run_path(w, data, num_splits=splits, want_lse=True, softmax_scale=scale)
+    want, want_lse = oracle_rows(oracle, w, data, None, softmax_scale=scale)
+    got, got_lse = to_host_f32(r["out"]), to_host_f32(r["lse"])
+    if dtype == "f32":
+        assert np.isfinite(got).all() and np.max(np.abs(got - want)) <= F32_TOL
+        assert np.max(np.abs(got_lse - want_lse)) <= 1e-4
+    else:
+        check_bf16(got, want, name)
+        assert np.max(np.abs(got_lse - want_lse)) <= 2e-2
+        lay, heads = layout_heads(w, None, scale)
+        q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+        out = torch.full_like(q, float("nan"))
+        P.pevlm_block_prefill_attn_rope(q, k, v, out, lay, heads, w.rope_base)
+        P.pevlm_query_attn_rope(q, k, v, out, lay, heads, w.rope_base, num_splits=splits)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), r["out"].view(torch.int16))
+    default, _ = oracle_rows(oracle, w, data, None)
+    assert np.max(np.abs(default - want)) > 10 * (F32_TOL if dtype == "f32" else 1e-3)
+    # the default written out explicitly gives the default result
+    r2 = run_path(w, data, num_splits=splits, softmax_scale=float(1.0 / np.sqrt(D)))
+    r3 = run_path(w, data, num_splits=splits)
+    assert np.max(np.abs(to_host_f32(r2["out"]) - to_host_f32(r3["out"]))) <= (1e-6 if dtype == "f32" else 2.0 ** -8)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rotated_tensors_under_position_offsets(oracle, dtype):
+    """pevlm_rope_seq with per-sequence starting positions: rotated Q and K element by element
+    against the oracle's rotation at positions o_s + n (fp32: 2e-6; bf16: one rounding)."""
+    seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 100, 250, 0)]
+    offs = [37, 100000, 4096]
+    w = W.Workload("offs_" + dtype, 22, dtype, 4, 2, 128, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
+    data = W.generate(w)
+    r = run_path(w, data, pos_offset=offs)
+    pos = oracle.positions(oracle_layout(oracle, w), offs)
+    for key in ("q", "k"):
+        exact = oracle.rope(data[key], pos, w.rope_base)
+        err = np.abs(to_host_f32(r[key + "_rot"]) - exact)
+        if dtype == "bf16":
+            assert np.all(err <= np.abs(exact) * 2.0 ** -8 + 1e-6)
+        else:
+            assert err.max() <= 5e-6
+    # and the rotation without offsets is a different tensor (the offsets are really used)
+    r0 = run_path(w, data)
+    assert not torch.equal(r0["k_rot"], r["k_rot"])
+
+
 def test_roofline_probes_run_and_copy_is_exact():
     """The measurement-only entry points: the copy moves every byte, the MFMA loop reports its
     operation count, bad arguments are rejected before any launch."""
@@ -508,9 +592,9 @@ STREAM_CASES = [
 
 
 @pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs", STREAM_CASES, ids=[c[0] for c in STREAM_CASES])
-def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(name, dtype, Hq, Hkv, D, seqs):
+def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(oracle, name, dtype, Hq, Hkv, D, seqs):
     """Sink + first blocks, then the remaining blocks two at a time: every call writes exactly its
-    rows, and the pieces add up to pevlm_block_prefill_attn bit for bit."""
+    rows, the pieces add up to pevlm_block_prefill_attn bit for bit, and equal the oracle's rows."""
     w = W.Workload(name, 17, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
     data = W.generate(w)
     lay, heads = layout_heads(w)
@@ -544,6 +628,14 @@ def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(name, dtype, H
         first_call = False
     both_nan = torch.isnan(out) & torch.isnan(ref)
     assert torch.equal(torch.nan_to_num(out), torch.nan_to_num(ref)) and torch.equal(torch.isnan(out), both_nan)
+    # the rows written by the piecewise calls, directly against the oracle
+    data_rows = np.concatenate([np.arange(c0, c0 + S + C) for c0, (S, B, C, Q) in zip(w.cu_seqlens, seqs)])
+    want, _ = oracle_rows(oracle, w, data, data_rows)
+    got = to_host_f32(out[torch.from_numpy(data_rows).to(DEV)])
+    if dtype == "bf16":
+        check_bf16(got, want, name + "/pieces")
+    else:
+        assert np.isfinite(got).all() and np.max(np.abs(got - want)) <= F32_TOL
 
 
 WINDOW_CASES = [
@@ -598,6 +690,55 @@ def test_windowed_question_full_size_c3(oracle):
     olay = oracle.Layout(a["cu_seqlens"], a["sink_len"], a["block_len"], a["ctx_len"], a["query_len"], window_blocks=[16])
     want, _ = oracle.forward(data["q"], data["k"], data["v"], olay, w.rope_base, rows=qrows)
     check_bf16(to_host_f32(out[torch.from_numpy(qrows).to(DEV)]), want, "c3/window16")
+
+
+# ------------------------------------------------------------------------------------ guard bands
+def _guarded(nbytes, guard=4096):
+    """A device byte range of exactly `nbytes` with `guard` bytes of a known pattern on both sides."""
+    pad = (-nbytes) % 256
+    buf = torch.full((guard + nbytes + pad + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    return buf, buf[guard:guard + nbytes]
+
+
+def _guards_intact(buf, nbytes, guard=4096):
+    return bool((buf[:guard] == 0xA5).all()) and bool((buf[guard + nbytes:] == 0xA5).all())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_nothing_is_written_outside_out_lse_and_the_workspaces(dtype):
+    """out, lse and both workspaces sit between guard bands (workspaces sized exactly as the
+    *_workspace_bytes queries say); after all calls every guard byte still holds its pattern."""
+    seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)]
+    w = W.Workload("guards_" + dtype, 23, dtype, 8, 2, 128 if dtype == "bf16" else 64, 1.0e6, seqs, 0.5)
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    esz = 2 if dtype == "bf16" else 4
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    n_out = q.numel() * esz
+    n_lse = w.total_tokens * w.n_q_heads * 4
+    sizes = dict(out=n_out, lse=n_lse,
+                 wp=P.pevlm_block_prefill_workspace_bytes(lay, heads), wq=P.pevlm_query_workspace_bytes(lay, heads, 5))
+    if dtype == "bf16":
+        sizes["wpr"] = P.pevlm_block_prefill_rope_workspace_bytes(lay, heads)
+        sizes["wqr"] = P.pevlm_query_rope_workspace_bytes(lay, heads, 5)
+    bufs = {name: _guarded(n) for name, n in sizes.items()}
+    out = bufs["out"][1].view(tdt).view(q.shape)
+    lse = bufs["lse"][1].view(torch.float32).view(w.total_tokens, w.n_q_heads)
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, lse=lse, workspace=bufs["wp"][1])
+    P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=5, lse=lse, workspace=bufs["wq"][1])
+    torch.cuda.synchronize()
+    ref = out.clone()
+    if dtype == "bf16":
+        q2, k2 = to_device(data["q"]), to_device(data["k"])
+        P.pevlm_block_prefill_attn_rope(q2, k2, v, out, lay, heads, w.rope_base, lse=lse, workspace=bufs["wpr"][1])
+        P.pevlm_query_attn_rope(q2, k2, v, out, lay, heads, w.rope_base, num_splits=5, lse=lse, workspace=bufs["wqr"][1])
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+    for name, n in sizes.items():
+        assert _guards_intact(bufs[name][0], n), f"guard band of {name} overwritten"
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
 
 
 # ------------------------------------------------------------------------------------ graph capture
