@@ -129,6 +129,23 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * pevlm_query_attn for callers that cannot hand over (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels and
+ * bit-identical results, but the scratch memory (work list, row map, fp32 partials) is an array of
+ * PEVLM_STATIC_SCRATCH_BYTES that is part of the library's code object: every GPU the library runs
+ * on holds one copy until the process ends.  The call allocates and frees nothing and does not
+ * synchronise.  A call whose plan needs more than the array (what pevlm_query_workspace_bytes
+ * reports, minus its 256 bytes of slack) returns PEVLM_ERR_WORKSPACE_TOO_SMALL with nothing enqueued.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different
+ * streams, different threads) race and must be serialised by the caller.  The first call on a
+ * device looks up the array's device address (make that call outside a graph capture).
+ */
+#define PEVLM_STATIC_SCRATCH_BYTES (64u << 20)
+pevlm_status pevlm_query_attn_static(const void *q, const void *k, const void *v, void *out, float *lse,
+                                     const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits,
+                                     void *stream);
+
+/*
  * The two attention calls with the sequential RoPE step (Sec. "Position Encoding") folded in, so
  * that q is never read and re-written by a separate pass.  `q` holds UN-rotated queries and is not
  * modified: each workgroup rotates its query rows once, on the fly, at

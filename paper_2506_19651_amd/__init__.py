@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     pevlm_probe_copy,
     pevlm_probe_mfma_bf16,
     pevlm_query_attn,
+    pevlm_query_attn_static,
     pevlm_query_attn_mrope,
     pevlm_query_attn_rope,
     pevlm_query_attn_window,

@@ -68,6 +68,8 @@ def load_library():
         lib.pevlm_query_workspace_bytes.argtypes = [LP, HP, i32]
         lib.pevlm_query_attn.restype = ctypes.c_int
         lib.pevlm_query_attn.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, vp, ctypes.c_size_t, vp]
+        lib.pevlm_query_attn_static.restype = ctypes.c_int
+        lib.pevlm_query_attn_static.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, vp]
         lib.pevlm_block_prefill_rope_workspace_bytes.restype = ctypes.c_size_t
         lib.pevlm_block_prefill_rope_workspace_bytes.argtypes = [LP, HP]
         lib.pevlm_block_prefill_attn_rope.restype = ctypes.c_int
@@ -304,6 +306,11 @@ def pevlm_query_attn(q, k, v, out, layout: Layout, heads: Heads, num_splits: int
                                            heads.ref(), int(num_splits), _ptr(workspace), workspace.numel(),
                                            _stream_ptr(stream)))
     return workspace
+
+
+def pevlm_query_attn_static(q, k, v, out, layout: Layout, heads: Heads, num_splits: int = 0, lse=None, stream=None):
+    _check(load_library().pevlm_query_attn_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
+                                                  heads.ref(), int(num_splits), _stream_ptr(stream)))
 
 
 def _i32_array(values):

@@ -6,6 +6,8 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 
 #include "common.h"
 
@@ -179,18 +181,20 @@ static int64_t total_query_rows(const pevlm_layout *lay)
 // Compute units of the current device (256 when it cannot be queried, e.g. no GPU present).
 static int32_t compute_units()
 {
-    static int32_t cached[16] = {0};
+    static std::atomic<int32_t> cached[16];  // zero-initialised; racing first calls store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) { (void)hipGetLastError(); return 256; }
-    if (cached[dev] == 0) {
+    int32_t have = cached[dev].load(std::memory_order_relaxed);
+    if (have == 0) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
             (void)hipGetLastError();
             n = 256;
         }
-        cached[dev] = n;
+        have = n;
+        cached[dev].store(have, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return have;
 }
 
 // Split count when the caller leaves it to the library: the split kernel keeps two workgroups per
@@ -258,6 +262,35 @@ static QueryPlan plan_query(const pevlm_layout *lay, const pevlm_heads *h, int32
     if (fuse_rope) off += rope_table_bytes(p.total_q, h);  // one entry per compact question row
     p.bytes = off;
     return p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Library-owned scratch memory of pevlm_query_attn_static: one array per GPU, part of the code
+// object, alive until the process ends.  Host code never uses the array's name as an address: the
+// device address is looked up once per device and kept.
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PEVLM_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static pevlm_status scratch_of_current_device(void **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(PEVLM_ERR_UNSUPPORTED, "device index %d not below %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return PEVLM_OK;
 }
 
 }  // namespace pevlm
@@ -539,6 +572,30 @@ pevlm_status pevlm_query_attn(const void *q, const void *k, const void *v, void 
                               void *workspace, size_t workspace_bytes, void *stream)
 {
     return query_impl(q, k, v, out, lse, layout, heads, num_splits, workspace, workspace_bytes, stream, false, 0.0, nullptr);
+}
+
+pevlm_status pevlm_query_attn_static(const void *q, const void *k, const void *v, void *out, float *lse,
+                                     const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits, void *stream)
+{
+    // validate sizes before touching the device: the plan is what pevlm_query_attn would carve
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    if (num_splits < 0 || num_splits > PEVLM_MAX_SPLITS)
+        return fail(PEVLM_ERR_INVALID_ARG, "num_splits must be in [0, %d]", PEVLM_MAX_SPLITS);
+    const QueryPlan plan = plan_query(layout, heads, num_splits);
+    if (plan.bytes > (size_t)PEVLM_STATIC_SCRATCH_BYTES)
+        return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL,
+                    "pevlm_query_attn_static: this call needs %zu bytes of scratch, the built-in array holds %zu "
+                    "(use pevlm_query_attn with a caller workspace, or fewer splits)",
+                    plan.bytes, (size_t)PEVLM_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    st = scratch_of_current_device(&ws);
+    if (st != PEVLM_OK) return st;
+    // Every field of the scratch a launch reads (work list, row map, partials of every split, row
+    // and head) is written earlier in the same call on the same stream, so nothing needs clearing.
+    return query_impl(q, k, v, out, lse, layout, heads, num_splits, ws, PEVLM_STATIC_SCRATCH_BYTES, stream, false, 0.0, nullptr);
 }
 
 pevlm_status pevlm_block_prefill_attn_mrope(const void *q, void *k, const void *v, void *out, float *lse,
