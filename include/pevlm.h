@@ -229,6 +229,35 @@ typedef struct {
     int32_t seq, reserved;
 } pevlm_work_item;
 
+/* One unit of work of the streaming bf16 block-prefill kernel (head_dim 128 or 64, query heads in
+ * equal groups per KV head): up to 8 slots of at most 32 query rows of ONE region (the sink, or one
+ * context block) whose heads share one KV head, so that all slots need the same key tiles: keys
+ * [full_start, full_start + full_len) visible to every row (the sink, for a context block) and keys
+ * [diag_start, diag_start + diag_len) visible to row i iff key <= i.  Slot w is taken by wavefront w
+ * of the workgroup that processes the item; q_rows == 0 marks an unused slot.  Within a region the
+ * slots run over (group of 32 rows, query head of the KV group) with the head index fastest, so the
+ * 8 slots of an item lie within 64 rows of each other and need almost the same number of key tiles. */
+typedef struct {
+    int32_t full_start, full_len;
+    int32_t diag_start, diag_len;
+    int32_t kv_head, n_full_tiles, n_tiles, seq; /* tiles of 64 keys: full range first, then diagonal range */
+    struct {
+        int32_t q_start, q_rows; /* packed row of the slot's first query, rows (1..32, 0 = unused) */
+        int32_t head, reserved;  /* query head */
+    } slot[8];
+} pevlm_stream_item;
+
+/* 1 if pevlm_block_prefill_attn (and _blocks) runs the streaming kernel for this head descriptor
+ * (bf16, every KV head serving the same number of query heads), else 0: then the one-item-per-
+ * workgroup kernel and the pevlm_work_item list are used. */
+int32_t pevlm_prefill_uses_stream_kernel(const pevlm_heads *heads);
+/* Enumerates, on the host, exactly the stream-item list the device builder writes for
+ * pevlm_block_prefill_attn_blocks (first_block == NULL: every block and the sink, as
+ * pevlm_block_prefill_attn).  Returns the number of items, or -1 for invalid arguments. */
+int64_t pevlm_prefill_stream_items_host(const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *first_block,
+                                        const int32_t *num_blocks, int32_t with_sink, pevlm_stream_item *items,
+                                        int64_t capacity);
+
 /* Query rows per work item the kernels selected by `heads` use for the block-prefill call and for
  * the question call (-1 for an invalid descriptor). */
 int32_t pevlm_prefill_tile_rows(const pevlm_heads *heads);

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     Heads,
     Layout,
     PevlmError,
+    StreamItem,
     WorkItem,
     lib_path,
     load_library,
@@ -19,6 +20,8 @@ from .binding import (  # noqa: F401
     pevlm_block_prefill_workspace_bytes,
     pevlm_last_error,
     pevlm_prefill_tile_rows,
+    pevlm_prefill_stream_items_host,
+    pevlm_prefill_uses_stream_kernel,
     pevlm_prefill_worklist_host,
     pevlm_probe_copy,
     pevlm_probe_mfma_bf16,

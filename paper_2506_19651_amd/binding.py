@@ -41,6 +41,15 @@ class WorkItem(ctypes.Structure):
                                               "diag_len", "seq", "reserved")]
 
 
+class _StreamSlot(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("q_start", "q_rows", "head", "reserved")]
+
+
+class StreamItem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("full_start", "full_len", "diag_start", "diag_len", "kv_head",
+                                              "n_full_tiles", "n_tiles", "seq")] + [("slot", _StreamSlot * 8)]
+
+
 _lib = None
 
 
@@ -100,6 +109,11 @@ def load_library():
         lib.pevlm_prefill_tile_rows.argtypes = [HP]
         lib.pevlm_query_tile_rows.restype = i32
         lib.pevlm_query_tile_rows.argtypes = [HP]
+        lib.pevlm_prefill_uses_stream_kernel.restype = ctypes.c_int32
+        lib.pevlm_prefill_uses_stream_kernel.argtypes = [HP]
+        lib.pevlm_prefill_stream_items_host.restype = ctypes.c_int64
+        lib.pevlm_prefill_stream_items_host.argtypes = [LP, HP, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), i32,
+                                                        ctypes.POINTER(StreamItem), ctypes.c_int64]
         lib.pevlm_prefill_worklist_host.restype = ctypes.c_int64
         lib.pevlm_prefill_worklist_host.argtypes = [LP, i32, ctypes.POINTER(WorkItem), ctypes.c_int64]
         lib.pevlm_query_worklist_host.restype = ctypes.c_int64
@@ -375,6 +389,24 @@ def pevlm_prefill_worklist_host(layout: Layout, tile_rows: int):
         raise PevlmError(PEVLM_ERR_INVALID_ARG, pevlm_last_error())
     items = (WorkItem * max(n, 1))()
     lib.pevlm_prefill_worklist_host(layout.ref(), tile_rows, items, n)
+    return [items[i] for i in range(n)]
+
+
+def pevlm_prefill_uses_stream_kernel(heads: Heads) -> bool:
+    return bool(load_library().pevlm_prefill_uses_stream_kernel(heads.ref()))
+
+
+def pevlm_prefill_stream_items_host(layout: Layout, heads: Heads, first_block=None, num_blocks=None, with_sink: bool = True):
+    lib = load_library()
+    fbp = nbp = None
+    if first_block is not None:
+        _fb, fbp = _i32_array(first_block)
+        _nb, nbp = _i32_array(num_blocks)
+    n = lib.pevlm_prefill_stream_items_host(layout.ref(), heads.ref(), fbp, nbp, int(bool(with_sink)), None, 0)
+    if n < 0:
+        raise PevlmError(PEVLM_ERR_INVALID_ARG, pevlm_last_error())
+    items = (StreamItem * max(n, 1))()
+    lib.pevlm_prefill_stream_items_host(layout.ref(), heads.ref(), fbp, nbp, int(bool(with_sink)), items, n)
     return [items[i] for i in range(n)]
 
 

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -178,6 +179,46 @@ static int64_t total_query_rows(const pevlm_layout *lay)
     return n;
 }
 
+// The streaming bf16 block-prefill kernel applies when every KV head serves the same number of query
+// heads (it deals the heads of a KV head out over the wavefronts of a workgroup).
+static bool equal_head_groups(const pevlm_heads *h)
+{
+    const int32_t G = h->n_q_heads / h->n_kv_heads;
+    if (!h->kv_head_of_q) return true;
+    int32_t count[kMaxHeads] = {0};
+    for (int32_t i = 0; i < h->n_q_heads; ++i) count[h->kv_head_of_q[i]] += 1;
+    for (int32_t g = 0; g < h->n_kv_heads; ++g)
+        if (count[g] != G) return false;
+    return true;
+}
+
+// PEVLM_PREFILL_KERNEL=classic in the environment keeps the one-item-per-workgroup kernel for every
+// call (a diagnostic switch for timing comparisons; read once).
+static bool stream_kernel_enabled()
+{
+    static const bool enabled = [] {
+        const char *e = getenv("PEVLM_PREFILL_KERNEL");
+        return !(e && strcmp(e, "classic") == 0);
+    }();
+    return enabled;
+}
+
+static bool use_stream_kernel(const pevlm_heads *h)
+{
+    return h->dtype == PEVLM_BF16 && equal_head_groups(h) && stream_kernel_enabled();
+}
+
+static int64_t count_stream_items(const pevlm_layout *lay, const pevlm_heads *h, const Restrict &r = Restrict())
+{
+    const int32_t G = h->n_q_heads / h->n_kv_heads;
+    int64_t n = 0;
+    for (int32_t s = 0; s < lay->num_seqs; ++s)
+        n += stream_items_of_seq(lay->sink_len[s], lay->ctx_len[s] > 0 ? lay->block_len[s] : 1, lay->ctx_len[s], G, h->n_kv_heads,
+                                 r.first_block ? r.first_block[s] : 0, r.num_blocks ? r.num_blocks[s] : blocks_of(lay, s),
+                                 r.with_sink);
+    return n;
+}
+
 // Compute units of the current device (256 when it cannot be queried, e.g. no GPU present).
 static int32_t compute_units()
 {
@@ -348,6 +389,9 @@ static size_t prefill_workspace(const pevlm_layout *layout, const pevlm_heads *h
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
     size_t n = align256((size_t)count_prefill_items(layout, tile_rows_of(heads, false)) * sizeof(pevlm_work_item));
     if (fuse_rope) n += rope_table_bytes(layout->cu_seqlens[layout->num_seqs], heads);
+    // the streaming kernel's list (plain calls on bf16 tensors) lives in the same workspace
+    if (!fuse_rope && heads->dtype == PEVLM_BF16 && equal_head_groups(heads))
+        n = std::max(n, align256((size_t)count_stream_items(layout, heads) * sizeof(pevlm_stream_item)));
     return n + 256;
 }
 
@@ -394,6 +438,42 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
         return PEVLM_OK;
     }
     if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
+    if (!fuse_rope && use_stream_kernel(heads)) {
+        // ---- streaming kernel: resident workgroups walk a list of stream items
+        const int64_t n_stream = count_stream_items(layout, heads, sel);
+        if (n_stream > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
+        size_t need_s = prefill_workspace(layout, heads, false);
+        if (!workspace || workspace_bytes < need_s || ((uintptr_t)workspace & 255))
+            return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "prefill workspace needs %zu bytes, 256-byte aligned (got %zu)", need_s,
+                        workspace ? workspace_bytes : (size_t)0);
+        hipStream_t hs = (hipStream_t)stream;
+        pevlm_stream_item *sitems = (pevlm_stream_item *)workspace;
+        const int32_t G = heads->n_q_heads / heads->n_kv_heads;
+        int32_t offset = 0;
+        for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
+            SeqTable tab;
+            int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
+            fill_table(layout, s0, n, pos_offset, &tab, sel);
+            for (int32_t i = 0; i < n; ++i)
+                tab.item_base[i + 1] = tab.item_base[i] + stream_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], G, heads->n_kv_heads,
+                                                                              tab.sel_first[i], tab.sel_count[i], tab.sel_sink);
+            if (tab.item_base[n] > 0) {
+                hipError_t e = launch_build_stream_items(tab, G, heads->n_kv_heads, p.heads, sitems, offset, hs);
+                if (e != hipSuccess) return hip_fail(e, "stream-item builder launch");
+            }
+            offset += tab.item_base[n];
+        }
+        StreamParams sp;
+        sp.q = q; sp.k = k; sp.v = v; sp.out = out; sp.lse = lse;
+        sp.items = sitems;
+        sp.n_items = (int32_t)n_stream;
+        sp.n_q_heads = heads->n_q_heads;
+        sp.n_kv_heads = heads->n_kv_heads;
+        sp.scale = scale_of(heads);
+        hipError_t e = launch_attn_bf16_stream(sp, heads->head_dim, compute_units(), hs);
+        if (e != hipSuccess) return hip_fail(e, "block-prefill launch");
+        return PEVLM_OK;
+    }
     size_t need = prefill_workspace(layout, heads, fuse_rope);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
         return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "prefill workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
@@ -709,6 +789,39 @@ int64_t pevlm_prefill_worklist_blocks_host(const pevlm_layout *layout, int32_t t
             if (items && n < capacity)
                 items[n] = prefill_item_sel(layout->cu_seqlens[s], layout->sink_len[s], B, layout->ctx_len[s], tile_rows,
                                             first_block[s], with_sink, i, s);
+    }
+    return n;
+}
+
+int32_t pevlm_prefill_uses_stream_kernel(const pevlm_heads *heads)
+{
+    return check_heads(heads, nullptr) == PEVLM_OK && use_stream_kernel(heads) ? 1 : 0;
+}
+
+int64_t pevlm_prefill_stream_items_host(const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *first_block,
+                                        const int32_t *num_blocks, int32_t with_sink, pevlm_stream_item *items,
+                                        int64_t capacity)
+{
+    if (check_layout(layout) != PEVLM_OK) return -1;
+    HeadTable ht;
+    if (check_heads(heads, &ht) != PEVLM_OK) return -1;
+    if (!equal_head_groups(heads)) { fail(PEVLM_ERR_UNSUPPORTED, "query heads are not in equal groups per KV head"); return -1; }
+    Restrict sel;
+    sel.first_block = first_block;
+    sel.num_blocks = num_blocks;
+    sel.with_sink = first_block ? with_sink : 1;
+    if (check_restrict(layout, sel) != PEVLM_OK) return -1;
+    const int32_t G = heads->n_q_heads / heads->n_kv_heads;
+    int64_t n = 0;
+    for (int32_t s = 0; s < layout->num_seqs; ++s) {
+        int32_t B = layout->ctx_len[s] > 0 ? layout->block_len[s] : 1;
+        int32_t first = first_block ? first_block[s] : 0;
+        int32_t cnt = stream_items_of_seq(layout->sink_len[s], B, layout->ctx_len[s], G, heads->n_kv_heads, first,
+                                          num_blocks ? num_blocks[s] : blocks_of(layout, s), sel.with_sink);
+        for (int32_t i = 0; i < cnt; ++i, ++n)
+            if (items && n < capacity)
+                items[n] = stream_item(layout->cu_seqlens[s], layout->sink_len[s], B, layout->ctx_len[s], G, heads->n_kv_heads, first,
+                                       sel.with_sink, i, s, ht.head_order);
     }
     return n;
 }

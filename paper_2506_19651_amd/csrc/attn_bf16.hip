@@ -26,224 +26,10 @@
 // Variants: PARTIAL writes un-normalised fp32 partials (question attention, merged afterwards);
 // ROPEQ rotates the query rows in registers from a (cos, sin) table instead of expecting rotated
 // queries; items of <= 64 rows are taken for 2 or 4 heads of a KV group by one workgroup.
-#include "bf16_device.h"
+#include "attn_bf16_tile.h"
 #include "rope_math.h"
 
 namespace pevlm {
-
-template <int D>
-struct TileCfg {
-    static constexpr int KT = kKeyTile;        // keys per staged tile
-    static constexpr int ROWB = D * 2;         // bytes per K/V row
-    static constexpr int CH = D / 8;           // 16-byte chunks per row
-    static constexpr int NLD = KT * CH / 256;  // 16-byte loads each wavefront issues per tensor per tile
-    static constexpr int KSTEPS = D / 16;      // MFMA k-steps of Q K^T
-    static constexpr int DBLK = D / 32;        // 32-wide blocks of head_dim in O^T
-    static constexpr int VSW = CH / 4 - 1;     // V swizzle mask (64-byte granules per row - 1)
-    static constexpr int TILEB = KT * ROWB;    // bytes of one staged K (or V) tile
-    static constexpr int RPI = 1024 / ROWB;    // rows one wavefront-wide 16-byte-per-lane load covers
-};
-
-// per-lane LDS offsets (the XOR swizzles depend on the lane only)
-struct LaneOff {
-    int32_t k_row_off, k_swz, v_row_off, v_ch_lo, v_swz, g32;
-};
-
-// Global->LDS loads a wavefront slips between the MFMAs of a tile (its share of the next K tile
-// during the score MFMAs, of the current V tile during the value MFMAs): a wavefront-uniform base
-// address, per-lane byte offsets and the LDS address of the wave's first 1 KB piece.
-template <int NLD>
-struct TileLoads {
-    const void *base;
-    uint32_t off[NLD];
-    uint32_t lds;
-};
-
-constexpr float kRescaleStep = 8.f;  // log2 units the row maximum may outgrow the reference maximum
-
-// S^T = K Q^T for the 64 keys of a staged tile: two independent accumulation chains (one per
-// 32-key chunk) issued alternately; A fragments (16 bytes per lane) are fetched half a tile ahead.
-template <int D, bool LOADS>
-__device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2],
-                                        const TileLoads<D / 32> &ld)
-{
-    using C = TileCfg<D>;
-    constexpr int HK = C::KSTEPS / 2;
-    const f32x16 init = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    bf16x8 a0[C::KSTEPS], a1[C::KSTEPS];
-#define PEVLM_KFRAG(kc, kk) \
-    (*reinterpret_cast<const bf16x8 *>(tk + (kc) * 32 * C::ROWB + L.k_row_off + ((((kk) * 2 + L.g32) ^ L.k_swz) << 4)))
-#pragma unroll
-    for (int kk = 0; kk < HK; ++kk) {
-        a0[kk] = PEVLM_KFRAG(0, kk);
-        a1[kk] = PEVLM_KFRAG(1, kk);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = 0; kk < HK; ++kk) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], kk == 0 ? init : s[0], 0, 0, 0);
-        a0[kk + HK] = PEVLM_KFRAG(0, kk + HK);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], kk == 0 ? init : s[1], 0, 0, 0);
-        a1[kk + HK] = PEVLM_KFRAG(1, kk + HK);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = HK; kk < C::KSTEPS; ++kk) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[kk], qf[kk], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], s[1], 0, 0, 0);
-        if (LOADS) {  // one 1 KB piece of the next K tile per pair of MFMAs
-            load_lds_16_base(ld.base, ld.off[kk - HK], ld.lds + (kk - HK) * 4096);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-#undef PEVLM_KFRAG
-}
-
-// V^T fragments of 16 keys (k-step ks of the staged tile) for every 32-wide block of head_dim
-template <int D>
-__device__ __forceinline__ void read_v(const uint8_t *tv, const LaneOff &L, int ks, bf16x8 (&dst)[D / 32])
-{
-    using C = TileCfg<D>;
-#pragma unroll
-    for (int b = 0; b < C::DBLK; ++b)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const uint8_t *ptr = tv + (ks * 16 + tt * 8) * C::ROWB + L.v_row_off + (((b ^ L.v_swz) * 4 + L.v_ch_lo) << 4);
-            const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));
-            const bf16x4 rb = __builtin_bit_cast(bf16x4, r);
-            dst[b][tt * 4 + 0] = rb[0]; dst[b][tt * 4 + 1] = rb[1];
-            dst[b][tt * 4 + 2] = rb[2]; dst[b][tt * 4 + 3] = rb[3];
-        }
-}
-
-// entries a row must not see: beyond the key range, or (causal range) keys after the row.  Key
-// k0 + c is visible iff c <= min(kend - 1, causal ? my_row : inf) - k0; c = const + 4*g32 per entry,
-// so each entry costs one compare against a per-lane limit and one select.
-__device__ __forceinline__ void mask_tile(f32x16 (&s)[2], int32_t k0, int32_t kend, bool causal, int32_t my_row, int32_t g32)
-{
-    int32_t last = kend - 1;
-    if (causal) last = my_row < last ? my_row : last;
-    const int32_t lim = last - k0 - g32 * 4;
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int32_t c = kc * 32 + (i >> 2) * 8 + (i & 3);
-            s[kc][i] = c <= lim ? s[kc][i] : -INFINITY;
-        }
-}
-
-// maximum over the 64 keys of the tile for this lane's row (both lanes of a row end up with it)
-__device__ __forceinline__ float row_max(const f32x16 (&s)[2])
-{
-    float mx = max3f(s[0][0], s[0][1], s[0][2]);
-#pragma unroll
-    for (int i = 3; i < 31; i += 2) mx = max3f(mx, s[i >> 4][i & 15], s[(i + 1) >> 4][(i + 1) & 15]);
-    mx = fmaxf(mx, s[1][15]);
-    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-}
-
-// weights p = exp2(c s - m) of the tile (c = scale*log2(e), m = the row's reference maximum in
-// base-2 units): bf16 pairs (B fragments of the value MFMAs) and their sum over this lane's 32 keys
-// (dot product of each pair with (1, 1)).  Weights are non-negative, so a sum below 2^kRescaleStep
-// bounds every one of them; an overflowed or invalid weight makes the sum inf or nan.
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-__device__ __forceinline__ uint32_t weight_pair(float s0, float s1, float c_log2, float mref, float &psum)
-{
-    bf16x2 pr;
-    pr[0] = (__bf16)__builtin_amdgcn_exp2f(s0 * c_log2 - mref);
-    pr[1] = (__bf16)__builtin_amdgcn_exp2f(s1 * c_log2 - mref);
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-    return __builtin_bit_cast(uint32_t, pr);
-}
-
-__device__ __forceinline__ void weights(const f32x16 (&s)[2], float c_log2, float mref, float &psum, u32x4 (&pf)[4])
-{
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) pf[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum);
-}
-
-// true unless this lane's sum of weights proves that all of them stayed below 2^kRescaleStep
-__device__ __forceinline__ bool sum_reached_step(float psum) { return !(psum < 256.f); }
-static_assert(kRescaleStep == 8.f, "sum_reached_step compares with 2^kRescaleStep");
-
-// O^T += V^T P^T for a staged V tile (16 MFMAs per 32 values of head_dim ... 4 k-steps x DBLK blocks)
-template <int D>
-__device__ __forceinline__ void pv_tile(const uint8_t *tv, const LaneOff &L, const u32x4 (&pf)[4], f32x16 (&o)[D / 32])
-{
-    using C = TileCfg<D>;
-    bf16x8 va[C::DBLK], vb[C::DBLK];
-    read_v<D>(tv, L, 0, va);
-#pragma unroll
-    for (int ks = 0; ks < 4; ks += 2) {
-        read_v<D>(tv, L, ks + 1, vb);
-#pragma unroll
-        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[b], __builtin_bit_cast(bf16x8, pf[ks]), o[b], 0, 0, 0);
-        if (ks + 2 < 4) read_v<D>(tv, L, ks + 2, va);
-#pragma unroll
-        for (int b = 0; b < C::DBLK; ++b) o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[b], __builtin_bit_cast(bf16x8, pf[ks + 1]), o[b], 0, 0, 0);
-    }
-}
-
-// One V^T fragment: 16 keys (k-step ks) x the b-th 32-wide block of head_dim
-template <int D>
-__device__ __forceinline__ bf16x8 read_v_one(const uint8_t *tv, const LaneOff &L, int ks, int b)
-{
-    using C = TileCfg<D>;
-    bf16x8 dst;
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        const uint8_t *ptr = tv + (ks * 16 + tt * 8) * C::ROWB + L.v_row_off + (((b ^ L.v_swz) * 4 + L.v_ch_lo) << 4);
-        const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ptr));
-        const bf16x4 rb = __builtin_bit_cast(bf16x4, r);
-        dst[tt * 4 + 0] = rb[0]; dst[tt * 4 + 1] = rb[1];
-        dst[tt * 4 + 2] = rb[2]; dst[tt * 4 + 3] = rb[3];
-    }
-    return dst;
-}
-
-// The pipelined step: O^T += V^T P^T of the previous tile (matrix cores) issued one MFMA at a time,
-// each followed by the vector-ALU work for a pair (or two) of weights of the current tile, so that
-// both pipes of the SIMD run from one instruction stream.  V^T fragments are read one k-step ahead.
-template <int D>
-__device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
-                                                    f32x16 (&o)[D / 32], const f32x16 (&s)[2], float c_log2,
-                                                    float mref, float &psum, u32x4 (&pf_new)[4], const TileLoads<D / 32> &ld)
-{
-    using C = TileCfg<D>;
-    constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
-    constexpr int PPM = 16 / NM;     // weight pairs formed per MFMA
-    bf16x8 vf[2][C::DBLK];
-#pragma unroll
-    for (int b = 0; b < C::DBLK; ++b) vf[0][b] = read_v_one<D>(tv_prev, L, 0, b);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int n = 0; n < NM; ++n) {
-        const int ks = n / C::DBLK, b = n % C::DBLK;
-        if (ks + 1 < 4) vf[(ks + 1) & 1][b] = read_v_one<D>(tv_prev, L, ks + 1, b);
-        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1][b], __builtin_bit_cast(bf16x8, pf_prev[ks]), o[b], 0, 0, 0);
-        if (n % 4 == 0) load_lds_16_base(ld.base, ld.off[n / 4], ld.lds + (n / 4) * 4096);  // a piece of the current V tile
-#pragma unroll
-        for (int e = 0; e < PPM; ++e) {
-            const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;
-            pf_new[kc * 2 + (i >> 3)][(i & 7) >> 1] = weight_pair(s[kc][i], s[kc][i + 1], c_log2, mref, psum);
-        }
-        // keep the running values here (plain arithmetic would otherwise be emitted after the last MFMA)
-        asm volatile("" : "+v"(psum));
-        if (((n + 1) * PPM) % 4 == 0) asm volatile("" : "+v"(pf_new[((n + 1) * PPM) / 4 - 1]));
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
 
 // ROPEQ: q holds un-rotated queries; each wavefront rotates its 32 rows once, right after loading
 // them, from the (cos, sin) table of the call (the sequential positions of Sec. "Position Encoding").
@@ -251,7 +37,7 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 // (KV head group, item, head in group).
 template <int D, bool PARTIAL, bool ROPEQ>
 __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, int32_t heads_inner, int32_t pack_heads,
-                                          uint8_t *lds_k, uint8_t *lds_v)
+                                          int32_t identity_map, uint8_t *lds_k, uint8_t *lds_v)
 {
     using C = TileCfg<D>;
     constexpr int KT = C::KT, ROWB = C::ROWB, CH = C::CH, NLD = C::NLD, KSTEPS = C::KSTEPS, DBLK = C::DBLK;
@@ -263,7 +49,11 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
     const int32_t item_idx = p.n_items - 1 - rest % p.n_items;
     const int32_t hs = (rest / p.n_items) * heads_inner + inner;
     const pevlm_work_item it = p.items[item_idx];
-    const int32_t g = __builtin_amdgcn_readfirstlane((int32_t)p.heads.kv_of_q[p.heads.head_order[hs]]);  // workgroup-uniform
+    // With the default head map (query head h on KV head h / G, schedule order = head order) both
+    // indices are plain arithmetic; the tables live in kernel-argument memory and looking them up
+    // costs two dependent memory round trips before the first query row can be requested.
+    const int32_t g = identity_map ? rest / p.n_items
+                                   : __builtin_amdgcn_readfirstlane((int32_t)p.heads.kv_of_q[p.heads.head_order[hs]]);  // workgroup-uniform
     const int32_t Hq = p.n_q_heads, Hkv = p.n_kv_heads;
 
     const int32_t tid = threadIdx.x, lane = tid & 63;
@@ -279,7 +69,8 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
     if (hpw > 1 && (inner % hpw) != 0) return;
     const int32_t slot = hpw > 1 ? inner + wave / wph : inner;
     const bool head_ok = slot < heads_inner;
-    const int32_t h = __builtin_amdgcn_readfirstlane((int32_t)p.heads.head_order[hs - inner + (head_ok ? slot : inner)]);  // wavefront-uniform
+    const int32_t h = identity_map ? hs - inner + (head_ok ? slot : inner)
+                                   : __builtin_amdgcn_readfirstlane((int32_t)p.heads.head_order[hs - inner + (head_ok ? slot : inner)]);  // wavefront-uniform
     const int32_t rg = hpw > 1 ? wave % wph : wave;  // this wave's group of 32 rows
     const int32_t l32 = lane & 31, g32 = lane >> 5;
     const uint16_t *Q = (const uint16_t *)p.q, *K = (const uint16_t *)p.k, *V = (const uint16_t *)p.v;
@@ -321,14 +112,6 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
     constexpr int WSLICE = 32 * ROWB;  // bytes of 32 rows
     uint8_t *const wave_slice = (wave < 2 ? lds_k : lds_v) + TILEB + (wave & 1) * WSLICE;
     const uint32_t wave_slice_addr = (wave < 2 ? lds_k_addr : lds_v_addr) + TILEB + (wave & 1) * WSLICE;
-#pragma unroll
-    for (int j = 0; j < WSLICE / 1024; ++j) {
-        const int32_t rl = j * RPI + lane / CH, cpos = lane % CH;
-        int32_t r = rg * 32 + rl;
-        r = r < it.q_rows ? r : it.q_rows - 1;
-        load_lds_16(Q + ((int64_t)(it.q_start + r) * Hq + h) * D + ((cpos ^ (rl & (CH - 1))) << 3),
-                    wave_slice_addr + j * 1024);
-    }
 
     const int32_t n_full_tiles = (it.full_len + KT - 1) / KT;
     const int32_t n_diag_tiles = (it.diag_len + KT - 1) / KT;
@@ -426,12 +209,21 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
         _Pragma("unroll") for (int j = 0; j < NLD; ++j) ld.off[j] = toff[j];                          \
     } while (0)
 
+    // First the K and V tiles of tile 0 (stage 0; they usually come from L2), then the query rows
+    // (first touch: from HBM), so that all three are in flight together.
     if (n_tiles > 0) {
         PEVLM_ISSUE_K(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | NLD);  // all but the K(0) loads: Q has landed
-    } else {
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        PEVLM_ISSUE_V(0);
     }
+#pragma unroll
+    for (int j = 0; j < WSLICE / 1024; ++j) {
+        const int32_t rl = j * RPI + lane / CH, cpos = lane % CH;
+        int32_t r = rg * 32 + rl;
+        r = r < it.q_rows ? r : it.q_rows - 1;
+        load_lds_16(Q + ((int64_t)(it.q_start + r) * Hq + h) * D + ((cpos ^ (rl & (CH - 1))) << 3),
+                    wave_slice_addr + j * 1024);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     asm volatile("" ::: "memory");
     const float c_log2 = p.scale * 1.4426950408889634f;
     bf16x8 qf[KSTEPS];
@@ -508,8 +300,11 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
     float psum;
     TileLoads<NLD> ldk, ldv;
     bool k_mod = false, v_mod = false;
+    if (n_tiles > 0) {  // top of tile 0 for every wavefront
+        __syncthreads();  // K(0), V(0) of every wavefront have landed; the query slices in stage 1 have been read
+        if (1 < n_tiles) PEVLM_ISSUE_K(1);
+    }
     if (n_w > 0) {
-        PEVLM_TOP(0);
         PEVLM_SCORES(0, false);
         psum = 0.f;  // no row has a reference yet: the first tile always takes the exact path
         PEVLM_FIX_REFERENCE();
@@ -552,7 +347,7 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
     }
     // Every wavefront passes the top of all n_tiles tiles and one final barrier.  The values of the
     // last tile a wave computed are added once their V tile is known to be in LDS.
-    int32_t t_rest = n_w;
+    int32_t t_rest = n_w > 0 ? n_w : (n_tiles > 0 ? 1 : 0);  // the top of tile 0 is behind every wavefront
     bool synced = false;
     if (n_w > 0 && n_w < n_tiles) {
         PEVLM_TOP(n_w);
@@ -623,14 +418,15 @@ __device__ __forceinline__ void attn_item(const AttnParams &p, int32_t logical, 
 // with its own L2); every XCD gets one contiguous run of logical ids so that the heads of a GQA
 // group working on the same context block share that XCD's L2.
 template <int D, bool PARTIAL, bool ROPEQ>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads)
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p, int32_t n_logical, int32_t heads_inner, int32_t pack_heads,
+                                                           int32_t identity_map)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t lds_k[2 * TileCfg<D>::TILEB];
     __shared__ __attribute__((aligned(1024))) uint8_t lds_v[2 * TileCfg<D>::TILEB];
     const int32_t per_xcd = gridDim.x >> 3;
     const int32_t logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= n_logical) return;
-    attn_item<D, PARTIAL, ROPEQ>(p, logical, heads_inner, pack_heads, lds_k, lds_v);
+    attn_item<D, PARTIAL, ROPEQ>(p, logical, heads_inner, pack_heads, identity_map, lds_k, lds_v);
 }
 
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream)
@@ -641,11 +437,14 @@ hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStr
     for (int32_t i = 0; i < p.n_q_heads; ++i)
         if (p.heads.kv_of_q[p.heads.head_order[i]] != i / G) uniform = false;
     int32_t heads_inner = uniform ? G : p.n_q_heads;
+    int32_t identity = uniform ? 1 : 0;  // query head h on KV head h / G, scheduled in head order
+    for (int32_t i = 0; i < p.n_q_heads; ++i)
+        if (p.heads.head_order[i] != i || p.heads.kv_of_q[i] != i / G) identity = 0;
     int32_t pack = (uniform && G > 1) ? 1 : 0;  // short items are taken for several heads of a KV group at once
     int32_t n_logical = p.n_items * p.n_q_heads;
     dim3 grid((n_logical + 7) / 8 * 8), block(256);
 #define PEVLM_ATTN_LAUNCH(DD, PP, RR) \
-    hipLaunchKernelGGL((attn_bf16_kernel<DD, PP, RR>), grid, block, 0, stream, p, n_logical, heads_inner, pack)
+    hipLaunchKernelGGL((attn_bf16_kernel<DD, PP, RR>), grid, block, 0, stream, p, n_logical, heads_inner, pack, identity)
     const bool rope = p.rope_tab != nullptr;
     if (D == 128) {
         if (partial) { if (rope) PEVLM_ATTN_LAUNCH(128, true, true); else PEVLM_ATTN_LAUNCH(128, true, false); }

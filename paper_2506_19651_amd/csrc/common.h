@@ -113,6 +113,91 @@ __host__ __device__ inline pevlm_work_item prefill_item_sel(int32_t start, int32
     return prefill_item(start, S, B, C, tile_rows, full_idx, seq);
 }
 
+// ------------------------------------------------------------------------------------------
+// Stream items of the block-prefill call (bf16 streaming kernel): a region of R rows is cut into
+// ceil(R/32) row groups; the slots (row group, head of the KV group), head fastest, are dealt out 8 at
+// a time.  Order inside a sequence: region (sink, then the selected blocks), then KV head, then item.
+// ------------------------------------------------------------------------------------------
+constexpr int32_t kSlotRows = 32;
+constexpr int32_t kSlotsPerItem = 8;
+
+__host__ __device__ inline int32_t stream_items_of_region(int32_t R, int32_t G)
+{
+    return R > 0 ? ceil_div(G * ceil_div(R, kSlotRows), kSlotsPerItem) : 0;
+}
+
+// Items of one sequence restricted to the sink (if with_sink) and context blocks [first, first + count).
+__host__ __device__ inline int32_t stream_items_of_seq(int32_t S, int32_t B, int32_t C, int32_t G, int32_t Hkv, int32_t first,
+                                                       int32_t count, int32_t with_sink)
+{
+    int32_t n = with_sink ? stream_items_of_region(S, G) : 0;
+    if (C > 0 && count > 0) {
+        int32_t nb = ceil_div(C, B);
+        int32_t last = C - (nb - 1) * B;
+        int32_t full = (first + count == nb) ? count - 1 : count;
+        n += full * stream_items_of_region(B, G);
+        if (first + count == nb) n += stream_items_of_region(last, G);
+    }
+    return n * Hkv;
+}
+
+// idx-th stream item of a sequence that starts at packed row `start`.  head_order (may be NULL =
+// identity) lists the query heads grouped by KV head: heads of KV head g are entries g*G .. g*G+G-1.
+__host__ __device__ inline pevlm_stream_item stream_item(int32_t start, int32_t S, int32_t B, int32_t C, int32_t G, int32_t Hkv,
+                                                         int32_t first, int32_t with_sink, int32_t idx, int32_t seq,
+                                                         const uint8_t *head_order)
+{
+    pevlm_stream_item it;
+    int32_t sink_items = with_sink ? stream_items_of_region(S, G) * Hkv : 0;
+    int32_t R, r_start, in_region;  // rows of the region, its first local position, item index inside it
+    if (idx < sink_items) {  // Eq. 3
+        R = S;
+        r_start = 0;
+        in_region = idx;
+        it.full_start = start;
+        it.full_len = 0;
+    } else {  // Eq. 4: the whole sink plus the block itself up to the diagonal
+        int32_t j = idx - sink_items;
+        int32_t per_block = stream_items_of_region(B, G) * Hkv;
+        int32_t nb = ceil_div(C, B);
+        int32_t b = first + j / per_block;
+        if (b >= nb) b = nb - 1;  // items of a short last block: fewer than per_block, all beyond the full blocks
+        in_region = j - (b - first) * per_block;
+        R = (C - b * B < B) ? C - b * B : B;
+        r_start = S + b * B;
+        it.full_start = start;
+        it.full_len = S;
+    }
+    int32_t per_head = stream_items_of_region(R, G);
+    int32_t g = in_region / per_head, jj = in_region % per_head;
+    int32_t n_slots = G * ceil_div(R, kSlotRows);
+    it.diag_start = start + r_start;
+    it.kv_head = g;
+    it.seq = seq;
+    int32_t row_end = 0;
+    for (int32_t w = 0; w < kSlotsPerItem; ++w) {
+        int32_t k = jj * kSlotsPerItem + w;
+        if (k < n_slots) {
+            int32_t r0 = (k / G) * kSlotRows;
+            int32_t rows = (R - r0 < kSlotRows) ? R - r0 : kSlotRows;
+            int32_t hs = g * G + k % G;
+            it.slot[w].q_start = start + r_start + r0;
+            it.slot[w].q_rows = rows;
+            it.slot[w].head = head_order ? (int32_t)head_order[hs] : hs;
+            row_end = r0 + rows;
+        } else {
+            it.slot[w].q_start = start + r_start;
+            it.slot[w].q_rows = 0;
+            it.slot[w].head = 0;
+        }
+        it.slot[w].reserved = 0;
+    }
+    it.diag_len = row_end;
+    it.n_full_tiles = ceil_div(it.full_len, 64);
+    it.n_tiles = it.n_full_tiles + ceil_div(it.diag_len, 64);
+    return it;
+}
+
 // Question items (Eq. 5): tiles of question rows x key splits.  The keys of a sequence
 // [start, start + L) are cut into num_splits runs of split_len keys; everything before the
 // question is visible to every question row, keys inside the question are causal.
@@ -217,6 +302,16 @@ struct AttnParams {
     HeadTable heads;
 };
 
+struct StreamParams {
+    const void *q, *k, *v;
+    void *out;     // [T][Hq][D] bf16
+    float *lse;    // [T][Hq] or nullptr
+    const pevlm_stream_item *items;
+    int32_t n_items;
+    int32_t n_q_heads, n_kv_heads;
+    float scale;
+};
+
 struct MergeParams {
     const float *part_acc, *part_ml;
     const int32_t *qrow_of_compact;  // [total_q_rows] packed row of each compact question row
@@ -244,6 +339,10 @@ hipError_t launch_rope_table(float *table, const int32_t *row_of_entry, const Se
                              hipStream_t stream);
 hipError_t launch_rope_mrope(void *q, void *k, int64_t T, int32_t Hq, int32_t Hkv, int32_t D, bool bf16, double rope_base,
                              const int32_t *pos3, int32_t sec0, int32_t sec01, float *table, hipStream_t stream);
+hipError_t launch_build_stream_items(const SeqTable &tab, int32_t G, int32_t Hkv, const HeadTable &heads,
+                                     pevlm_stream_item *items, int32_t item_offset, hipStream_t stream);
+// block-prefill rows of bf16 tensors from a stream-item list; workgroups = compute units (8 wavefronts each)
+hipError_t launch_attn_bf16_stream(const StreamParams &p, int32_t D, int32_t compute_units, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);  // p.rope_tab selects the fused variant
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);

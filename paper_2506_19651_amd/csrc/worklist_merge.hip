@@ -41,6 +41,28 @@ __global__ __launch_bounds__(256) void build_query_items_kernel(SeqTable tab, in
             qrow_of_compact[tab.qrow_base[s] + r] = tab.start[s] + tab.sink[s] + tab.ctx[s] + r;
 }
 
+// Same for the stream items of the bf16 streaming block-prefill kernel (item_base counts stream items).
+__global__ __launch_bounds__(256) void build_stream_items_kernel(SeqTable tab, int32_t G, int32_t Hkv, HeadTable heads,
+                                                                 pevlm_stream_item *items, int32_t item_offset)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    int32_t total = tab.item_base[tab.num_seqs];
+    if (i >= total) return;
+    int32_t s = 0;
+    while (s + 1 < tab.num_seqs && i >= tab.item_base[s + 1]) ++s;
+    items[item_offset + i] = stream_item(tab.start[s], tab.sink[s], tab.block[s], tab.ctx[s], G, Hkv, tab.sel_first[s], tab.sel_sink,
+                                         i - tab.item_base[s], tab.seq_index0 + s, heads.head_order);
+}
+
+hipError_t launch_build_stream_items(const SeqTable &tab, int32_t G, int32_t Hkv, const HeadTable &heads,
+                                     pevlm_stream_item *items, int32_t item_offset, hipStream_t stream)
+{
+    int32_t total = tab.item_base[tab.num_seqs];
+    hipLaunchKernelGGL(build_stream_items_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, tab, G, Hkv, heads, items,
+                       item_offset);
+    return hipGetLastError();
+}
+
 hipError_t launch_build_prefill_items(const SeqTable &tab, int32_t tile_rows, pevlm_work_item *items,
                                       int32_t item_offset, hipStream_t stream)
 {

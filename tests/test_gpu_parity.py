@@ -139,6 +139,21 @@ def test_bf16_hard_softmax_cases(oracle, name, extra, seqs, splits):
     assert np.all(lse_err <= 2e-2 + 1e-4 * np.abs(want_lse))
 
 
+def prefill_list_on_device(ws, lay, heads):
+    """True if the work list the block-prefill call left in its workspace equals the host enumeration
+    (stream items for the streaming bf16 kernel, plain work items otherwise)."""
+    if P.pevlm_prefill_uses_stream_kernel(heads):
+        host = P.pevlm_prefill_stream_items_host(lay, heads)
+        size = ctypes.sizeof(P.StreamItem)
+        host_bytes = b"".join(bytes(it) for it in host)
+    else:
+        host = P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads))
+        size = ctypes.sizeof(P.WorkItem)
+        host_bytes = b"".join(bytes(it) for it in host)
+    assert len(host) > 0
+    return ws.cpu().numpy()[: len(host) * size].tobytes() == host_bytes
+
+
 def test_bf16_gpu_worklist_equals_host_enumeration():
     seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)]
     w = W.Workload("wl", 13, "bf16", 4, 2, 128, 1.0e6, seqs, 0.5)
@@ -148,11 +163,7 @@ def test_bf16_gpu_worklist_equals_host_enumeration():
     out = torch.zeros_like(q)
     ws = P.pevlm_block_prefill_attn(q, k, v, out, lay, heads)
     torch.cuda.synchronize()
-    host = P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads))
-    n = len(host)
-    dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
-    host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
-    assert np.array_equal(dev_items, host_items)
+    assert prefill_list_on_device(ws, lay, heads)
     ws = P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=5)
     torch.cuda.synchronize()
     host = P.pevlm_query_worklist_host(lay, P.pevlm_query_tile_rows(heads), 5)
@@ -518,16 +529,17 @@ def test_batches_larger_than_one_sequence_table(oracle, dtype):
     lay, heads = layout_heads(w)
     q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
     out = torch.zeros_like(q)
-    for ws, host in ((P.pevlm_block_prefill_attn(q, k, v, out, lay, heads),
-                      P.pevlm_prefill_worklist_host(lay, P.pevlm_prefill_tile_rows(heads))),
-                     (P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=3),
-                      P.pevlm_query_worklist_host(lay, P.pevlm_query_tile_rows(heads), 3))):
-        torch.cuda.synchronize()
-        n = len(host)
-        assert n > 100
-        dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
-        host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
-        assert np.array_equal(dev_items, host_items)
+    ws = P.pevlm_block_prefill_attn(q, k, v, out, lay, heads)
+    torch.cuda.synchronize()
+    assert prefill_list_on_device(ws, lay, heads)
+    ws = P.pevlm_query_attn(q, k, v, out, lay, heads, num_splits=3)
+    host = P.pevlm_query_worklist_host(lay, P.pevlm_query_tile_rows(heads), 3)
+    torch.cuda.synchronize()
+    n = len(host)
+    assert n > 100
+    dev_items = ws.cpu().numpy()[: n * 32].view(np.int32).reshape(n, 8)
+    host_items = np.array([[getattr(it, f) for f, _ in P.WorkItem._fields_] for it in host], np.int32)
+    assert np.array_equal(dev_items, host_items)
 
 
 # ------------------------------------------------------------------------------------ seeded sweep

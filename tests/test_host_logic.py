@@ -75,6 +75,72 @@ def test_prefill_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows):
     assert len(items) == n_expected
 
 
+def expand_stream_items(items, T, Hq):
+    """cover[row, head] = how many slots own it; M[head][row, key] = how often the key is offered to the row."""
+    cover = np.zeros((T, Hq), np.int32)
+    M = np.zeros((Hq, T, T), np.uint8)
+    for it in items:
+        assert it.n_full_tiles == -(-it.full_len // 64) and it.n_tiles == it.n_full_tiles + -(-it.diag_len // 64)
+        assert it.n_tiles >= 1
+        used = [sl for sl in it.slot if sl.q_rows > 0]
+        assert used and all(1 <= sl.q_rows <= 32 for sl in used)
+        # the item's diagonal range reaches exactly its last row
+        assert it.diag_start + it.diag_len == max(sl.q_start + sl.q_rows for sl in used)
+        for sl in used:
+            for r in range(sl.q_start, sl.q_start + sl.q_rows):
+                cover[r, sl.head] += 1
+                M[sl.head, r, it.full_start:it.full_start + it.full_len] += 1
+                hi = min(it.diag_start + it.diag_len, r + 1)
+                assert hi > it.diag_start
+                M[sl.head, r, it.diag_start:hi] += 1
+    return cover, M
+
+
+STREAM_HEADS = [(4, 2, None), (7, 1, None), (8, 2, [1, 0, 0, 1, 1, 0, 1, 0]), (3, 3, None)]
+
+
+@pytest.mark.parametrize("seqs", LAYOUTS)
+@pytest.mark.parametrize("Hq,Hkv,hmap", STREAM_HEADS)
+def test_stream_items_expand_to_oracle_mask(oracle, seqs, Hq, Hkv, hmap):
+    lay = P.Layout.from_seqs(seqs)
+    heads = P.Heads(Hq, Hkv, 128, "bf16", hmap)
+    assert P.pevlm_prefill_uses_stream_kernel(heads)
+    T = lay.total_tokens
+    olay = oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q)
+    want = oracle.mask_matrix(olay)
+    items = P.pevlm_prefill_stream_items_host(lay, heads)
+    cover, M = expand_stream_items(items, T, Hq)
+    G = Hq // Hkv
+    kv = hmap if hmap is not None else [h // G for h in range(Hq)]
+    for it in items:
+        assert all(kv[sl.head] == it.kv_head for sl in it.slot if sl.q_rows > 0)
+    t0 = 0
+    for (S, B, C, Q) in seqs:
+        assert np.all(cover[t0:t0 + S + C] == 1) and np.all(cover[t0 + S + C:t0 + S + C + Q] == 0)
+        for h in range(Hq):
+            assert np.array_equal(M[h, t0:t0 + S + C], want[t0:t0 + S + C])
+        t0 += S + C + Q
+
+
+def test_stream_items_of_a_block_selection_and_unequal_groups():
+    seqs = [(70, 100, 350, 9), (0, 33, 99, 0)]
+    lay = P.Layout.from_seqs(seqs)
+    heads = P.Heads(4, 2, 128, "bf16")
+    full = P.pevlm_prefill_stream_items_host(lay, heads)
+    key = lambda it: (it.seq, it.diag_start, it.kv_head, it.slot[0].q_start, it.slot[0].head)
+    sel = P.pevlm_prefill_stream_items_host(lay, heads, [1, 0], [3, 2], with_sink=False)
+    fullmap = {key(it): bytes(it) for it in full}
+    assert len(sel) > 0 and all(fullmap[key(it)] == bytes(it) for it in sel)
+    rows = sorted({r for it in sel for sl in it.slot if sl.q_rows for r in range(sl.q_start, sl.q_start + sl.q_rows)})
+    assert rows == list(range(70 + 100, 70 + 350)) + list(range(429, 429 + 66))
+    # unequal groups per KV head: the one-item kernel is used instead
+    uneven = P.Heads(4, 2, 128, "bf16", [0, 0, 0, 1])
+    assert not P.pevlm_prefill_uses_stream_kernel(uneven)
+    assert not P.pevlm_prefill_uses_stream_kernel(P.Heads(4, 2, 64, "f32"))
+    with pytest.raises(P.PevlmError):
+        P.pevlm_prefill_stream_items_host(lay, uneven)
+
+
 @pytest.mark.parametrize("seqs", LAYOUTS)
 @pytest.mark.parametrize("tile_rows,num_splits", [(16, 1), (16, 3), (128, 4), (128, 64), (1, 2)])
 def test_query_worklist_expands_to_oracle_mask(oracle, seqs, tile_rows, num_splits):
