@@ -247,10 +247,17 @@ typedef struct {
     } slot[8];
 } pevlm_stream_item;
 
-/* 1 if pevlm_block_prefill_attn (and _blocks) runs the streaming kernel for this head descriptor
- * (bf16, every KV head serving the same number of query heads), else 0: then the one-item-per-
- * workgroup kernel and the pevlm_work_item list are used. */
-int32_t pevlm_prefill_uses_stream_kernel(const pevlm_heads *heads);
+/* 1 if pevlm_block_prefill_attn runs the streaming kernel for this layout and head descriptor on the
+ * current device, else 0: then the one-item-per-workgroup kernel and the pevlm_work_item list are
+ * used.  The streaming kernel needs bf16 tensors, every KV head serving the same number of query
+ * heads, and fewer than 2 GiB per K (or V) tensor; left to itself the library takes it when the list
+ * holds at least 12 stream items per compute unit and no sink or block is longer than 16384 rows. */
+int32_t pevlm_prefill_uses_stream_kernel(const pevlm_layout *layout, const pevlm_heads *heads);
+/* Process-wide choice of that kernel, for timing comparisons and tests: 0 = per call as described
+ * above (the default; the environment variable PEVLM_PREFILL_KERNEL=classic|stream sets the start
+ * value 1 or 2), 1 = always the one-item-per-workgroup kernel, 2 = the streaming kernel wherever it
+ * applies.  Results are bit-identical either way.  Returns the previous value, or -1 for a bad mode. */
+int32_t pevlm_set_prefill_kernel(int32_t mode);
 /* Enumerates, on the host, exactly the stream-item list the device builder writes for
  * pevlm_block_prefill_attn_blocks (first_block == NULL: every block and the sink, as
  * pevlm_block_prefill_attn).  Returns the number of items, or -1 for invalid arguments. */

@@ -39,6 +39,7 @@ from .binding import (  # noqa: F401
     pevlm_query_worklist_host,
     pevlm_rope_mrope,
     pevlm_rope_seq,
+    pevlm_set_prefill_kernel,
     pevlm_version,
     pevlm_visible_pairs,
 )

@@ -110,7 +110,9 @@ def load_library():
         lib.pevlm_query_tile_rows.restype = i32
         lib.pevlm_query_tile_rows.argtypes = [HP]
         lib.pevlm_prefill_uses_stream_kernel.restype = ctypes.c_int32
-        lib.pevlm_prefill_uses_stream_kernel.argtypes = [HP]
+        lib.pevlm_prefill_uses_stream_kernel.argtypes = [LP, HP]
+        lib.pevlm_set_prefill_kernel.restype = ctypes.c_int32
+        lib.pevlm_set_prefill_kernel.argtypes = [i32]
         lib.pevlm_prefill_stream_items_host.restype = ctypes.c_int64
         lib.pevlm_prefill_stream_items_host.argtypes = [LP, HP, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), i32,
                                                         ctypes.POINTER(StreamItem), ctypes.c_int64]
@@ -392,8 +394,17 @@ def pevlm_prefill_worklist_host(layout: Layout, tile_rows: int):
     return [items[i] for i in range(n)]
 
 
-def pevlm_prefill_uses_stream_kernel(heads: Heads) -> bool:
-    return bool(load_library().pevlm_prefill_uses_stream_kernel(heads.ref()))
+def pevlm_prefill_uses_stream_kernel(layout: Layout, heads: Heads) -> bool:
+    return bool(load_library().pevlm_prefill_uses_stream_kernel(layout.ref(), heads.ref()))
+
+
+def pevlm_set_prefill_kernel(mode) -> int:
+    """mode: 0 / "auto", 1 / "classic", 2 / "stream"; returns the previous mode (int)."""
+    code = {"auto": 0, "classic": 1, "stream": 2}.get(mode, mode)
+    prev = int(load_library().pevlm_set_prefill_kernel(int(code)))
+    if prev < 0:
+        raise PevlmError(PEVLM_ERR_INVALID_ARG, "prefill kernel mode must be 0, 1 or 2")
+    return prev
 
 
 def pevlm_prefill_stream_items_host(layout: Layout, heads: Heads, first_block=None, num_blocks=None, with_sink: bool = True):

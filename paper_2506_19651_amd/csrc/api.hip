@@ -192,20 +192,40 @@ static bool equal_head_groups(const pevlm_heads *h)
     return true;
 }
 
-// PEVLM_PREFILL_KERNEL=classic in the environment keeps the one-item-per-workgroup kernel for every
-// call (a diagnostic switch for timing comparisons; read once).
-static bool stream_kernel_enabled()
+// Which kernel serves the block-prefill call on bf16 tensors: 0 = chosen per call (below), 1 = always the
+// one-item-per-workgroup kernel, 2 = the streaming kernel whenever it applies.  Process-wide; starts
+// from PEVLM_PREFILL_KERNEL=classic|stream in the environment (anything else: 0).
+static std::atomic<int32_t> &prefill_kernel_mode()
 {
-    static const bool enabled = [] {
+    static std::atomic<int32_t> mode([] {
         const char *e = getenv("PEVLM_PREFILL_KERNEL");
-        return !(e && strcmp(e, "classic") == 0);
-    }();
-    return enabled;
+        return e && strcmp(e, "classic") == 0 ? 1 : (e && strcmp(e, "stream") == 0 ? 2 : 0);
+    }());
+    return mode;
 }
 
-static bool use_stream_kernel(const pevlm_heads *h)
+// The streaming kernel needs equal head groups and bf16 tensors, and addresses a key range through
+// 32-bit byte offsets from the range's first row.
+static bool stream_kernel_applies(const pevlm_layout *lay, const pevlm_heads *h)
 {
-    return h->dtype == PEVLM_BF16 && equal_head_groups(h) && stream_kernel_enabled();
+    const int64_t T = lay->cu_seqlens[lay->num_seqs];
+    return h->dtype == PEVLM_BF16 && equal_head_groups(h) && T * h->n_kv_heads * h->head_dim * 2 < ((int64_t)1 << 31);
+}
+
+// It deals whole items out to one resident workgroup per compute unit; with only a few items per
+// workgroup the shares come out too uneven, and the one-item-per-workgroup kernel (two small workgroups
+// per compute unit, dispatched as slots free up) finishes sooner.  So it does on regions far longer
+// than any block the method uses (a dense causal attention written as one block: measured 8 % faster at
+// 64K rows), where the key stream of an item no longer stays in the L2 of its XCD.
+constexpr int32_t kMinStreamItemsPerWorkgroup = 12;
+constexpr int32_t kMaxStreamRegionRows = 16384;
+
+static bool regions_fit_stream_kernel(const pevlm_layout *lay)
+{
+    for (int32_t s = 0; s < lay->num_seqs; ++s)
+        if (lay->sink_len[s] > kMaxStreamRegionRows || (lay->ctx_len[s] > 0 && std::min(lay->block_len[s], lay->ctx_len[s]) > kMaxStreamRegionRows))
+            return false;
+    return true;
 }
 
 static int64_t count_stream_items(const pevlm_layout *lay, const pevlm_heads *h, const Restrict &r = Restrict())
@@ -217,6 +237,17 @@ static int64_t count_stream_items(const pevlm_layout *lay, const pevlm_heads *h,
                                  r.first_block ? r.first_block[s] : 0, r.num_blocks ? r.num_blocks[s] : blocks_of(lay, s),
                                  r.with_sink);
     return n;
+}
+
+static int32_t compute_units();
+
+// Stream items of the call if the streaming kernel is to run it, else 0.
+static int64_t stream_items_if_chosen(const pevlm_layout *lay, const pevlm_heads *h, const Restrict &r, bool fuse_rope)
+{
+    const int32_t mode = prefill_kernel_mode().load(std::memory_order_relaxed);
+    if (fuse_rope || mode == 1 || !stream_kernel_applies(lay, h)) return 0;
+    const int64_t n = count_stream_items(lay, h, r);
+    return (mode == 2 || (n >= (int64_t)kMinStreamItemsPerWorkgroup * compute_units() && regions_fit_stream_kernel(lay))) ? n : 0;
 }
 
 // Compute units of the current device (256 when it cannot be queried, e.g. no GPU present).
@@ -438,9 +469,9 @@ static pevlm_status prefill_impl(const void *q, const void *k, const void *v, vo
         return PEVLM_OK;
     }
     if (n_items * heads->n_q_heads > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
-    if (!fuse_rope && use_stream_kernel(heads)) {
+    const int64_t n_stream = stream_items_if_chosen(layout, heads, sel, fuse_rope);
+    if (n_stream > 0) {
         // ---- streaming kernel: resident workgroups walk a list of stream items
-        const int64_t n_stream = count_stream_items(layout, heads, sel);
         if (n_stream > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
         size_t need_s = prefill_workspace(layout, heads, false);
         if (!workspace || workspace_bytes < need_s || ((uintptr_t)workspace & 255))
@@ -793,9 +824,16 @@ int64_t pevlm_prefill_worklist_blocks_host(const pevlm_layout *layout, int32_t t
     return n;
 }
 
-int32_t pevlm_prefill_uses_stream_kernel(const pevlm_heads *heads)
+int32_t pevlm_prefill_uses_stream_kernel(const pevlm_layout *layout, const pevlm_heads *heads)
 {
-    return check_heads(heads, nullptr) == PEVLM_OK && use_stream_kernel(heads) ? 1 : 0;
+    if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;
+    return stream_items_if_chosen(layout, heads, Restrict(), false) > 0 ? 1 : 0;
+}
+
+int32_t pevlm_set_prefill_kernel(int32_t mode)
+{
+    if (mode < 0 || mode > 2) return -1;
+    return prefill_kernel_mode().exchange(mode);
 }
 
 int64_t pevlm_prefill_stream_items_host(const pevlm_layout *layout, const pevlm_heads *heads, const int32_t *first_block,

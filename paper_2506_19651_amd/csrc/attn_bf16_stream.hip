@@ -24,13 +24,6 @@ namespace pevlm {
 
 namespace {
 
-// position of the load stream: tile t of the workgroup's item number ord
-struct TileCursor {
-    int32_t ord, t;
-    int32_t n_full, n_tiles;
-    int32_t full_start, full_len, diag_start, diag_len, g;
-};
-
 __device__ __forceinline__ int32_t sgpr(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // Field `idx` (in 32-bit words) of a stream item, read through the constant address space: the address
@@ -45,31 +38,6 @@ __device__ __forceinline__ int32_t item_word(const pevlm_stream_item *it, int32_
     return sgpr(((const_i32_ptr)(uintptr_t)it)[idx]);
 }
 static_assert(sizeof(pevlm_stream_item) == (F_SLOT0 + 8 * S_WORDS) * 4, "stream item layout");
-
-__device__ __forceinline__ void cursor_set(TileCursor &c, const pevlm_stream_item *it, int32_t ord)
-{
-    c.ord = ord;
-    c.t = 0;
-    c.n_full = item_word(it, F_N_FULL);
-    c.n_tiles = item_word(it, F_N_TILES);
-    c.full_start = item_word(it, F_FULL_START);
-    c.full_len = item_word(it, F_FULL_LEN);
-    c.diag_start = item_word(it, F_DIAG_START);
-    c.diag_len = item_word(it, F_DIAG_LEN);
-    c.g = item_word(it, F_KV_HEAD);
-}
-
-// key range of the cursor's tile: first key, end of its range
-__device__ __forceinline__ void cursor_range(const TileCursor &c, int32_t &k0, int32_t &kend)
-{
-    if (c.t < c.n_full) {
-        k0 = c.full_start + c.t * kKeyTile;
-        kend = c.full_start + c.full_len;
-    } else {
-        k0 = c.diag_start + (c.t - c.n_full) * kKeyTile;
-        kend = c.diag_start + c.diag_len;
-    }
-}
 
 #define PEVLM_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 // the same with a compile-time count
@@ -88,6 +56,46 @@ __device__ __forceinline__ int32_t opaque(int32_t v)
     return v;
 }
 
+// ---- loads through a buffer descriptor (base address + byte count in scalar registers).  A lane's
+// address is base + scalar offset + its own byte offset; an address at or beyond the byte count reads
+// as zero instead of touching memory.  A key range (or a slot's query rows) gets a descriptor whose
+// byte count ends with its last row, so rows past the end arrive as zeros: masked scores, zero values.
+// Per tile only scalar registers change; the per-lane offsets are constants of the kernel.
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+__device__ __forceinline__ i32x4 make_rsrc(uint64_t base, uint32_t bytes)
+{
+    i32x4 r;
+    r[0] = sgpr((int32_t)(uint32_t)base);
+    r[1] = sgpr((int32_t)((uint32_t)(base >> 32) & 0xffffu));  // stride 0: raw buffer
+    r[2] = sgpr((int32_t)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+// 16 bytes per lane straight into LDS at lds_addr + 16 * lane (lds_addr wavefront-uniform)
+__device__ __forceinline__ void load_lds_16_buf(const i32x4 &rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds\n" ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+// the loads of one tensor for one tile step: piece j of the wavefront lies `sstep` bytes further in
+// memory (32 or 64 rows) and PSTEP bytes further in LDS
+template <int PSTEP>
+struct BufTileLoads {
+    i32x4 rsrc;
+    uint32_t voff, soff, sstep, lds;
+    __device__ __forceinline__ void issue(int j) const { load_lds_16_buf(rsrc, voff, soff + j * sstep, lds + j * PSTEP); }
+};
+
+// position of the load stream: tile t of the workgroup's item number ord, with the two key ranges of
+// that item as (byte address of the first K row of the KV head, bytes up to the end of the range)
+struct TileCursor {
+    int32_t ord, t;
+    int32_t n_full, n_tiles;
+    uint64_t base_full, base_diag;
+    uint32_t bytes_full, bytes_diag;
+};
+
 }  // namespace
 
 template <int D>
@@ -97,14 +105,13 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
     constexpr int KT = C::KT, ROWB = C::ROWB, CH = C::CH, KSTEPS = C::KSTEPS, DBLK = C::DBLK;
     constexpr int VSW = C::VSW, TILEB = C::TILEB, RPI = C::RPI;
     constexpr int NW = 8;                         // wavefronts per workgroup
-    constexpr int NLW = 8;                        // wavefronts that issue the K/V tile loads (the first NLW; all of them)
-    constexpr int NL = KT * CH / (64 * NLW);      // 16-byte loads a loading wavefront issues per tensor per tile
+    constexpr int NL = KT * CH / (64 * NW);       // 16-byte loads a wavefront issues per tensor per tile
     constexpr int TL = 2 * NL;                    // ... per tile step (K and V)
-    constexpr int PSTEP = NLW * 1024;             // LDS distance between a wavefront's pieces of a tile
+    constexpr int PSTEP = NW * 1024;              // LDS distance between a wavefront's pieces of a tile
     constexpr int NST = 3;                        // LDS stages per tensor
     constexpr int WSLICE = 32 * ROWB;             // a wavefront's query / output slice
     constexpr int NQL = WSLICE / 1024;            // loads per query slice
-    static_assert(NL >= 1 && NL <= 4, "tile loads per wavefront");
+    static_assert(NL >= 1 && NL <= 2 && (NW * RPI) % 16 == 0, "tile loads per wavefront");
     __shared__ __attribute__((aligned(1024))) uint8_t lds[2 * NST * TILEB + NW * WSLICE];
 
     // ---- the items of this workgroup: every XCD takes one contiguous eighth of the list (its L2 then
@@ -122,7 +129,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
     const int32_t wave = sgpr(tid >> 6);
     const int32_t l32 = lane & 31, g32 = lane >> 5;
     const int32_t Hq = p.n_q_heads, Hkv = p.n_kv_heads;
-    const uint16_t *Q = (const uint16_t *)p.q, *K = (const uint16_t *)p.k, *V = (const uint16_t *)p.v;
 
     LaneOff L;
     L.g32 = g32;
@@ -138,74 +144,86 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
     const uint32_t lds_v_addr = (uint32_t)(size_t)LDS_PTR(void, lds_v);
     const uint32_t slice_addr = (uint32_t)(size_t)LDS_PTR(void, slice);
 
-    // ---- K/V tile loads: a wavefront instruction fills 1 KB of LDS = RPI whole rows; which 16-byte
-    // chunk of the row a lane fetches carries the XOR swizzle (K by row & 15, V by (row & 3) << 2).
-    // Rows past the end of the key range repeat its last key (masked scores, finite values).
-    int32_t piece_row[NL];
-#pragma unroll
-    for (int j = 0; j < NL; ++j) piece_row[j] = (j * NLW + (wave & (NLW - 1))) * RPI + lane / CH;
-    // (Letting only the first four wavefronts, one per SIMD, carry the load stream -- NLW = 4 -- was
-    // measured slower than sharing it.)
-    const bool loader = NLW == NW ? true : wave < NLW;
-    const int32_t cpos = lane % CH;
-    const int32_t row_bytes = Hkv * D * 2;
-    // offsets of this lane's pieces for a tile whose last valid key is `last` (0..KT-1)
-#define PEVLM_KV_OFFSETS(koff, voff, last)                                                              \
-    _Pragma("unroll") for (int j = 0; j < NL; ++j) {                                                    \
-        const int32_t key = piece_row[j] < (last) ? piece_row[j] : (last);                              \
-        koff[j] = (uint32_t)(key * row_bytes + ((cpos ^ (piece_row[j] & (CH - 1))) << 4));              \
-        voff[j] = (uint32_t)(key * row_bytes + ((cpos ^ ((piece_row[j] & VSW) << 2)) << 4));            \
+    // ---- K/V tile loads: a wavefront instruction fills 1 KB of LDS = RPI whole rows of the tile, piece
+    // j of wavefront w being rows (j * NW + w) * RPI ...; which 16-byte chunk of the row a lane fetches
+    // carries the XOR swizzle (K by row & 15, V by (row & 3) << 2), the same for every piece of a lane
+    // (pieces are a multiple of 16 rows apart).
+    const uint32_t kv_row_bytes = (uint32_t)(Hkv * D * 2);
+    const uint32_t tile_bytes = KT * kv_row_bytes;
+    const int64_t v_minus_k = (int64_t)((uint64_t)p.v - (uint64_t)p.k);
+    BufTileLoads<PSTEP> ldk, ldv;
+    {
+        const int32_t row0 = wave * RPI + lane / CH, cpos = lane % CH;
+        ldk.voff = (uint32_t)row0 * kv_row_bytes + (uint32_t)((cpos ^ (row0 & (CH - 1))) << 4);
+        ldv.voff = (uint32_t)row0 * kv_row_bytes + (uint32_t)((cpos ^ ((row0 & VSW) << 2)) << 4);
+        ldk.sstep = ldv.sstep = NW * RPI * kv_row_bytes;
     }
 
-    // ---- load stream state.  kc is the tile whose K is loaded next; the V loads of a tile follow
-    // one tile later and use the range remembered in (v_k0, v_last, v_g).
+    // ---- load stream state.  kc is the tile whose K is loaded next; the V loads of a tile follow one
+    // tile later and use the descriptor remembered in (v_base, v_bytes, v_soff).
     TileCursor kc;
-    cursor_set(kc, PEVLM_ITEM(0), 0);
-    int32_t v_k0 = 0, v_last = 0, v_g = 0;
+#define PEVLM_CURSOR_SET(ord_)                                                                          \
+    do {                                                                                                \
+        const pevlm_stream_item *ci_ = PEVLM_ITEM(ord_);                                                \
+        const int32_t g_ = item_word(ci_, F_KV_HEAD);                                                   \
+        const int32_t fs_ = item_word(ci_, F_FULL_START), fl_ = item_word(ci_, F_FULL_LEN);             \
+        const int32_t ds_ = item_word(ci_, F_DIAG_START), dl_ = item_word(ci_, F_DIAG_LEN);             \
+        kc.n_full = item_word(ci_, F_N_FULL);                                                           \
+        kc.n_tiles = item_word(ci_, F_N_TILES);                                                         \
+        kc.ord = (ord_);                                                                                \
+        kc.t = 0;                                                                                       \
+        kc.base_full = (uint64_t)p.k + ((uint64_t)((int64_t)fs_ * Hkv + g_) * D) * 2;                   \
+        kc.base_diag = (uint64_t)p.k + ((uint64_t)((int64_t)ds_ * Hkv + g_) * D) * 2;                   \
+        kc.bytes_full = (uint32_t)fl_ * kv_row_bytes;                                                   \
+        kc.bytes_diag = (uint32_t)dl_ * kv_row_bytes;                                                   \
+    } while (0)
+    PEVLM_CURSOR_SET(0);
+    uint64_t v_base = 0;
+    uint32_t v_bytes = 0, v_soff = 0;
     // advances kc by one tile (into the next item at the end of one; stays on the last tile of the last item)
 #define PEVLM_CURSOR_ADVANCE()                                        \
     do {                                                              \
         if (kc.t + 1 < kc.n_tiles) {                                  \
             kc.t += 1;                                                \
         } else if (kc.ord + 1 < n_mine) {                             \
-            cursor_set(kc, PEVLM_ITEM(kc.ord + 1), kc.ord + 1);       \
+            const int32_t nord_ = kc.ord + 1;                         \
+            PEVLM_CURSOR_SET(nord_);                                  \
         }                                                             \
     } while (0)
-    // base pointers and per-lane offsets of the loads of one tile step: K of tile kc -> stage ks_ld, V of the
-    // tile before it -> stage vs_ld; then kc moves on
-#define PEVLM_TILE_LOADS_SETUP(ldk, ldv, ks_ld, vs_ld)                                                  \
+    // descriptors of the loads of one tile step: K of tile kc -> stage ks_ld, V of the tile before it ->
+    // stage vs_ld; then kc moves on
+#define PEVLM_TILE_LOADS_SETUP(ks_ld, vs_ld)                                                            \
     do {                                                                                                \
-        int32_t k0_, kend_;                                                                             \
-        cursor_range(kc, k0_, kend_);                                                                   \
-        const int32_t klast_ = kend_ - 1 - k0_ < KT - 1 ? kend_ - 1 - k0_ : KT - 1;                     \
-        uint32_t ko_[NL], vo_[NL], kx_[NL], vx_[NL];                                                    \
-        PEVLM_KV_OFFSETS(ko_, vx_, klast_);                                                             \
-        PEVLM_KV_OFFSETS(kx_, vo_, v_last);                                                             \
-        (void)vx_; (void)kx_;                                                                           \
-        ldk.base = uniform_ptr(K + ((int64_t)k0_ * Hkv + kc.g) * D);                                    \
-        ldv.base = uniform_ptr(V + ((int64_t)v_k0 * Hkv + v_g) * D);                                    \
-        ldk.lds = lds_k_addr + (ks_ld) * TILEB + (wave & (NLW - 1)) * 1024;                             \
-        ldv.lds = lds_v_addr + (vs_ld) * TILEB + (wave & (NLW - 1)) * 1024;                             \
-        _Pragma("unroll") for (int j = 0; j < NL; ++j) { ldk.off[j] = ko_[j]; ldv.off[j] = vo_[j]; }    \
-        v_k0 = k0_; v_last = klast_; v_g = kc.g;                                                        \
+        const bool full_ = kc.t < kc.n_full;                                                            \
+        const uint64_t kb_ = full_ ? kc.base_full : kc.base_diag;                                       \
+        const uint32_t kn_ = full_ ? kc.bytes_full : kc.bytes_diag;                                     \
+        const uint32_t so_ = (uint32_t)(full_ ? kc.t : kc.t - kc.n_full) * tile_bytes;                  \
+        ldk.rsrc = make_rsrc(kb_, kn_);                                                                 \
+        ldk.soff = so_;                                                                                 \
+        ldv.rsrc = make_rsrc(v_base, v_bytes);                                                          \
+        ldv.soff = v_soff;                                                                              \
+        ldk.lds = lds_k_addr + (ks_ld) * TILEB + wave * 1024;                                           \
+        ldv.lds = lds_v_addr + (vs_ld) * TILEB + wave * 1024;                                           \
+        v_base = kb_ + (uint64_t)v_minus_k; v_bytes = kn_; v_soff = so_;                                \
         PEVLM_CURSOR_ADVANCE();                                                                         \
     } while (0)
-#define PEVLM_TILE_LOADS_BURST(ldk, ldv)                                                                \
-    do {                                                                                                \
-        _Pragma("unroll") for (int j = 0; j < NL; ++j) load_lds_16_base(ldk.base, ldk.off[j], ldk.lds + j * PSTEP); \
-        _Pragma("unroll") for (int j = 0; j < NL; ++j) load_lds_16_base(ldv.base, ldv.off[j], ldv.lds + j * PSTEP); \
+#define PEVLM_TILE_LOADS_BURST()                                       \
+    do {                                                               \
+        _Pragma("unroll") for (int j = 0; j < NL; ++j) ldk.issue(j);   \
+        _Pragma("unroll") for (int j = 0; j < NL; ++j) ldv.issue(j);   \
     } while (0)
 
-    // ---- query slice loads: whole 256-byte rows, chunk-swizzled like a K tile; rows past the slot's
-    // last row repeat it.  An unused slot (or no further item) re-reads valid rows of the current one.
+    // ---- query slice loads: whole 256-byte rows of one head, chunk-swizzled like a K tile.  The
+    // descriptor ends with the slot's last row: rows past it (and every row of an unused slot, or of a
+    // prefetch past the last item: zero rows) arrive as zeros.
 #define PEVLM_ISSUE_Q(q_start, q_rows, head)                                                            \
     do {                                                                                                \
+        const uint32_t qrb_ = (uint32_t)(Hq * D * 2);                                                   \
+        const i32x4 rq_ = make_rsrc((uint64_t)p.q + ((uint64_t)((int64_t)(q_start) * Hq + (head)) * D) * 2, (uint32_t)(q_rows) * qrb_); \
         const int32_t ln_ = opaque(lane);                                                               \
         _Pragma("unroll") for (int j = 0; j < NQL; ++j) {                                               \
             const int32_t rl = j * RPI + ln_ / CH;                                                      \
-            const int32_t r = rl < (q_rows) ? rl : (q_rows) - 1;                                        \
-            load_lds_16(Q + ((int64_t)((q_start) + r) * Hq + (head)) * D + (((ln_ % CH) ^ (rl & (CH - 1))) << 3), \
-                        slice_addr + j * 1024);                                                         \
+            load_lds_16_buf(rq_, (uint32_t)rl * qrb_ + (uint32_t)(((ln_ % CH) ^ (rl & (CH - 1))) << 4), 0u, slice_addr + j * 1024); \
         }                                                                                               \
     } while (0)
 #define PEVLM_READ_QF()                                                                                 \
@@ -278,50 +296,36 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
         pend = 0;                                                                                     \
     } while (0)
 
-    // query rows of the item after next (the next item's are already in registers or in the slice)
+    // query rows of the item after next (the next item's are already in registers or in the slice); past
+    // the last item, or for an unused slot, a descriptor of zero rows: zeros arrive, no memory is touched
 #define PEVLM_PREFETCH_Q(ord_target)                                                                  \
     do {                                                                                              \
-        int32_t ps_ = q_start, pr_ = q_rows > 0 ? q_rows : 1, ph_ = head;                             \
+        int32_t ps_ = 0, pr_ = 0, ph_ = 0;                                                            \
         if ((ord_target) < n_mine) {                                                                  \
             const pevlm_stream_item *nx_ = PEVLM_ITEM(ord_target);                                    \
-            const int32_t r_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_Q_ROWS);                   \
-            if (r_ > 0) {                                                                             \
-                ps_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_Q_START);                           \
-                pr_ = r_;                                                                             \
-                ph_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_HEAD);                              \
-            }                                                                                         \
+            ps_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_Q_START);                               \
+            pr_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_Q_ROWS);                                \
+            ph_ = item_word(nx_, F_SLOT0 + wave * S_WORDS + S_HEAD);                                  \
         }                                                                                             \
         PEVLM_ISSUE_Q(ps_, pr_, ph_);                                                                 \
         q_age = 0;                                                                                    \
     } while (0)
 
     // ================= prologue: first tiles and the first item's queries =================
-    TileLoads<NL> ldk, ldv;
-    ldk.base = ldv.base = K;
-    ldk.lds = ldv.lds = 0;
-#pragma unroll
-    for (int j = 0; j < NL; ++j) ldk.off[j] = ldv.off[j] = 0;
-    if (loader) {
-        // K(0) -> stage 0, K(1) -> stage 1, V(0) -> stage 0; then kc stands on tile 2
-        int32_t k0_, kend_;
-        cursor_range(kc, k0_, kend_);
-        v_k0 = k0_; v_last = kend_ - 1 - k0_ < KT - 1 ? kend_ - 1 - k0_ : KT - 1; v_g = kc.g;
-        uint32_t ko_[NL], vo_[NL];
-        PEVLM_KV_OFFSETS(ko_, vo_, v_last);
-        const uint16_t *kb_ = uniform_ptr(K + ((int64_t)k0_ * Hkv + kc.g) * D);
-#pragma unroll
-        for (int j = 0; j < NL; ++j) load_lds_16_base(kb_, ko_[j], lds_k_addr + (wave & (NLW - 1)) * 1024 + j * PSTEP);
-        PEVLM_CURSOR_ADVANCE();
-        PEVLM_TILE_LOADS_SETUP(ldk, ldv, 1, 0);
-        PEVLM_TILE_LOADS_BURST(ldk, ldv);
+    {
+        // K(0) -> stage 0 (the V descriptor of this step is empty: zeros into V stage 2, which is rewritten
+        // before it is read), then K(1) -> stage 1 and V(0) -> stage 0; kc then stands on tile 2
+        PEVLM_TILE_LOADS_SETUP(0, 2);
+        PEVLM_TILE_LOADS_BURST();
+        PEVLM_TILE_LOADS_SETUP(1, 0);
+        PEVLM_TILE_LOADS_BURST();
     }
     {
         const pevlm_stream_item *it0 = PEVLM_ITEM(0);
         q_start = item_word(it0, F_SLOT0 + wave * S_WORDS + S_Q_START);
         q_rows = item_word(it0, F_SLOT0 + wave * S_WORDS + S_Q_ROWS);
         head = item_word(it0, F_SLOT0 + wave * S_WORDS + S_HEAD);
-        // an unused slot reads the first row of the region (valid memory), its result is never stored
-        PEVLM_ISSUE_Q(q_start, (q_rows > 0 ? q_rows : 1), head);
+        PEVLM_ISSUE_Q(q_start, q_rows, head);
         PEVLM_WAIT_VM(0);
         PEVLM_READ_QF();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -330,16 +334,16 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
     }
 
     int32_t ks = 0;  // LDS stage of the current tile's K; V of the previous tile sits in stage (ks + 2) % 3
-    // top of a tile: K(t) and V(t-1) of every wavefront have landed, everybody has left the previous tile;
-    // then the loads of this tile step are prepared (K(t+2) -> stage (ks+2)%3, V(t+1) -> stage (ks+1)%3)
+    // top of a tile: K(t) and V(t-1) of every wavefront have landed (the loads issued during the previous
+    // tile, and a query prefetch issued within the last two tiles, may still be in flight), everybody has
+    // left the previous tile; then the loads of this tile step are prepared (K(t+2) -> stage (ks+2)%3,
+    // V(t+1) -> stage (ks+1)%3)
 #define PEVLM_TOP()                                                                                   \
     do {                                                                                              \
-        if (loader) {                                                                                 \
-            if (q_age <= 2) wait_vm<TL + NQL>(); else wait_vm<TL>();                                  \
-        }                                                                                             \
+        if (q_age <= 2) wait_vm<TL + NQL>(); else wait_vm<TL>();                                      \
         __builtin_amdgcn_s_barrier();                                                                 \
         asm volatile("" ::: "memory");                                                                \
-        if (loader) PEVLM_TILE_LOADS_SETUP(ldk, ldv, (ks >= 1 ? ks - 1 : 2), (ks + 1 < NST ? ks + 1 : 0)); \
+        PEVLM_TILE_LOADS_SETUP((ks >= 1 ? ks - 1 : 2), (ks + 1 < NST ? ks + 1 : 0));                  \
     } while (0)
 #define PEVLM_NEXT_TILE()                  \
     do {                                   \
@@ -361,7 +365,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
     // this very tile is the youngest load; otherwise only this tile's K/V loads may still be in flight.
 #define PEVLM_END_OF_COMPUTE(ord)                                                                     \
     do {                                                                                              \
-        if (q_age == 0 || (!loader && q_age < 3)) {                                                   \
+        if (q_age == 0) {                                                                             \
             PEVLM_WAIT_VM(0);                                                                         \
         } else if (q_age < 3) {                                                                       \
             wait_vm<TL>();                                                                            \
@@ -404,7 +408,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
         // ---- tile 0: loads in one burst, the pending end of the previous item's slot, then the first
         // tile's exact softmax (no row has a reference maximum yet)
         PEVLM_TOP();
-        if (loader) PEVLM_TILE_LOADS_BURST(ldk, ldv);
+        PEVLM_TILE_LOADS_BURST();
         if (pend) {
             PEVLM_FINISH_PENDING();
             PEVLM_PREFETCH_Q(ord + 1);
@@ -417,7 +421,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
             PEVLM_TILE_RANGE(0, k0, kend, causal);
-            qk_tile_ring<D, false, NL, PSTEP>(lds_k + ks * TILEB, L, qf, s, ldk);
+            qk_tile_ring<D, false, NL>(lds_k + ks * TILEB, L, qf, s, ldk);
             if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo))) mask_tile(s, k0, kend, causal, my_row, g32);
             psum = 0.f;
             PEVLM_FIX_REFERENCE();
@@ -433,11 +437,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
         for (int32_t t = 1; t < n_w; ++t) {
             PEVLM_TOP();
             PEVLM_TILE_RANGE(t, k0, kend, causal);
-            const uint8_t *const tk = lds_k + ks * TILEB, *const tv = lds_v + (ks >= 1 ? ks - 1 : 2) * TILEB;
-            qk_tile_ring<D, true, NL, PSTEP>(tk, L, qf, s, ldk, loader);
+            qk_tile_ring<D, true, NL>(lds_k + ks * TILEB, L, qf, s, ldk);
             if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo))) mask_tile(s, k0, kend, causal, my_row, g32);
             psum = 0.f;
-            pv_prev_weights_cur_ring<D, NL, PSTEP>(tv, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, pf_new, ldv, loader);
+            pv_prev_weights_cur_ring<D, NL>(lds_v + (ks >= 1 ? ks - 1 : 2) * TILEB, L, pf_prev, o, s, c_log2, PEVLM_MREF, psum, pf_new, ldv);
             PEVLM_FIX_REFERENCE();
             l_run += psum;
 #pragma unroll
@@ -450,7 +453,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_stream_kernel(StreamParams p
         // loads; in the first of them the slot's last value tile and output
         for (int32_t t = n_w > 1 ? n_w : 1; t < n_tiles; ++t) {
             PEVLM_TOP();
-            if (loader) PEVLM_TILE_LOADS_BURST(ldk, ldv);
+            PEVLM_TILE_LOADS_BURST();
             if (pend) {
                 PEVLM_FINISH_PENDING();
                 PEVLM_PREFETCH_Q(ord + 2);

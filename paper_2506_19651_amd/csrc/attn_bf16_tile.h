@@ -82,10 +82,10 @@ __device__ __forceinline__ void qk_tile(const uint8_t *tk, const LaneOff &L, con
 
 // Same scores with the A fragments fetched only PF k-steps ahead of their MFMAs (a ring of PF
 // fragments per 32-key chunk instead of half a tile): fewer live registers, for the kernel that has
-// none to spare.
-template <int D, bool LOADS, int NL, int PSTEP, int PF = 2>
+// none to spare.  `ld.issue(j)` requests the wavefront's j-th piece (of NL) of a later K tile.
+template <int D, bool LOADS, int NL, class LD, int PF = 2>
 __device__ __forceinline__ void qk_tile_ring(const uint8_t *tk, const LaneOff &L, const bf16x8 (&qf)[D / 16], f32x16 (&s)[2],
-                                             const TileLoads<NL> &ld, bool on = true)
+                                             const LD &ld)
 {
     using C = TileCfg<D>;
     constexpr int KS = C::KSTEPS, HK = KS / 2;
@@ -105,8 +105,7 @@ __device__ __forceinline__ void qk_tile_ring(const uint8_t *tk, const LaneOff &L
         if (kk + PF < KS) a0[kk + PF] = PEVLM_KFRAG(0, kk + PF);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[kk], qf[kk], kk == 0 ? init : s[1], 0, 0, 0);
         if (kk + PF < KS) a1[kk + PF] = PEVLM_KFRAG(1, kk + PF);
-        if (LOADS && kk >= HK && kk - HK < NL && on)  // one 1 KB piece of a later K tile per pair of MFMAs
-            load_lds_16_base(ld.base, ld.off[kk - HK < NL ? kk - HK : 0], ld.lds + (kk - HK) * PSTEP);
+        if (LOADS && kk >= HK && kk - HK < NL) ld.issue(kk - HK);  // one 1 KB piece of a later K tile per pair of MFMAs
         __builtin_amdgcn_sched_barrier(0);
     }
 #undef PEVLM_KFRAG
@@ -255,12 +254,12 @@ __device__ __forceinline__ void pv_prev_weights_cur(const uint8_t *tv_prev, cons
 }
 
 // The same pipelined step with the V^T fragments fetched only PF MFMAs ahead (a ring of PF fragments
-// instead of two k-steps of them): fewer live registers.
-template <int D, int NL, int PSTEP, int PF = 3>
+// instead of two k-steps of them): fewer live registers.  `ld.issue(j)` requests the wavefront's j-th
+// piece (of NL) of a later V tile.
+template <int D, int NL, class LD, int PF = 3>
 __device__ __forceinline__ void pv_prev_weights_cur_ring(const uint8_t *tv_prev, const LaneOff &L, const u32x4 (&pf_prev)[4],
                                                          f32x16 (&o)[D / 32], const f32x16 (&s)[2], float c_log2,
-                                                         float mref, float &psum, u32x4 (&pf_new)[4], const TileLoads<NL> &ld,
-                                                         bool on = true)
+                                                         float mref, float &psum, u32x4 (&pf_new)[4], const LD &ld)
 {
     using C = TileCfg<D>;
     constexpr int NM = 4 * C::DBLK;  // MFMAs of the tile
@@ -274,7 +273,7 @@ __device__ __forceinline__ void pv_prev_weights_cur_ring(const uint8_t *tv_prev,
         const int ks = n / C::DBLK, b = n % C::DBLK;
         if (n + PF < NM) vf[n + PF] = read_v_one<D>(tv_prev, L, (n + PF) / C::DBLK, (n + PF) % C::DBLK);
         o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[n], __builtin_bit_cast(bf16x8, pf_prev[ks]), o[b], 0, 0, 0);
-        if (n % 4 == 0 && n / 4 < NL && on) load_lds_16_base(ld.base, ld.off[n / 4 < NL ? n / 4 : 0], ld.lds + (n / 4) * PSTEP);  // a piece of a V tile
+        if (n % 4 == 0 && n / 4 < NL) ld.issue(n / 4);
 #pragma unroll
         for (int e = 0; e < PPM; ++e) {
             const int pi = n * PPM + e, kc = pi >> 3, i = (pi & 7) * 2;

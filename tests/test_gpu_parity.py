@@ -20,6 +20,15 @@ BF16_MAX, BF16_MEAN, BF16_REL = 2e-2, 2e-3, 3e-2
 F32_TOL = 1e-5
 
 
+@pytest.fixture(params=["auto", "stream"])
+def prefill_kernel(request):
+    """Runs a test under the library's own choice of block-prefill kernel and with the streaming kernel
+    forced (small layouts would otherwise never reach it)."""
+    prev = P.pevlm_set_prefill_kernel(request.param)
+    yield request.param
+    P.pevlm_set_prefill_kernel(prev)
+
+
 def oracle_rows(oracle, w, data, rows, **kw):
     return oracle.forward(data["q"], data["k"], data["v"], oracle_layout(oracle, w), w.rope_base, rows=rows, **kw)
 
@@ -88,7 +97,7 @@ BF16_SMALL = [
 
 
 @pytest.mark.parametrize("name,Hq,Hkv,D,seqs,splits", BF16_SMALL, ids=[c[0] for c in BF16_SMALL])
-def test_bf16_small_all_rows(oracle, name, Hq, Hkv, D, seqs, splits):
+def test_bf16_small_all_rows(oracle, name, Hq, Hkv, D, seqs, splits, prefill_kernel):
     w = W.Workload(name, 12, "bf16", Hq, Hkv, D, 1.0e6, seqs, 0.5, key_offset_scale=0.3)
     data = W.generate(w)
     r = run_path(w, data, num_splits=splits, want_lse=True)
@@ -120,7 +129,7 @@ HARD = [
 
 
 @pytest.mark.parametrize("name,extra,seqs,splits", HARD, ids=[c[0] for c in HARD])
-def test_bf16_hard_softmax_cases(oracle, name, extra, seqs, splits):
+def test_bf16_hard_softmax_cases(oracle, name, extra, seqs, splits, prefill_kernel):
     """Inputs that drive the rare paths of the online softmax (reference maximum raised after the
     fact, overflow of the first-pass weights).  Compared with the oracle fed with the GPU's own
     rotated bf16 Q/K, so that only the attention arithmetic is under test."""
@@ -142,7 +151,7 @@ def test_bf16_hard_softmax_cases(oracle, name, extra, seqs, splits):
 def prefill_list_on_device(ws, lay, heads):
     """True if the work list the block-prefill call left in its workspace equals the host enumeration
     (stream items for the streaming bf16 kernel, plain work items otherwise)."""
-    if P.pevlm_prefill_uses_stream_kernel(heads):
+    if P.pevlm_prefill_uses_stream_kernel(lay, heads):
         host = P.pevlm_prefill_stream_items_host(lay, heads)
         size = ctypes.sizeof(P.StreamItem)
         host_bytes = b"".join(bytes(it) for it in host)
@@ -154,7 +163,7 @@ def prefill_list_on_device(ws, lay, heads):
     return ws.cpu().numpy()[: len(host) * size].tobytes() == host_bytes
 
 
-def test_bf16_gpu_worklist_equals_host_enumeration():
+def test_bf16_gpu_worklist_equals_host_enumeration(prefill_kernel):
     seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)]
     w = W.Workload("wl", 13, "bf16", 4, 2, 128, 1.0e6, seqs, 0.5)
     data = W.generate(w)
@@ -173,7 +182,7 @@ def test_bf16_gpu_worklist_equals_host_enumeration():
     assert np.array_equal(dev_items, host_items)
 
 
-def test_bf16_no_cross_block_leak_and_reproducible():
+def test_bf16_no_cross_block_leak_and_reproducible(prefill_kernel):
     """Exact checks: perturbing another block's K/V leaves a block's rows bit-identical; two runs
     give bit-identical outputs; keys a row must not see have exactly zero weight (V = 0 on visible
     keys, 1 elsewhere -> output exactly 0)."""
@@ -259,7 +268,7 @@ SCALE_CASES = [
 
 
 @pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs,scale,splits", SCALE_CASES, ids=[c[0] for c in SCALE_CASES])
-def test_caller_chosen_softmax_scale(oracle, name, dtype, Hq, Hkv, D, seqs, scale, splits):
+def test_caller_chosen_softmax_scale(oracle, name, dtype, Hq, Hkv, D, seqs, scale, splits, prefill_kernel):
     """Eq. 1 with the caller's factor in place of 1/sqrt(d): all three calls (and the pair with RoPE
     folded in), out and lse, against the oracle evaluated with the same factor; and the result
     differs from the default-scale one (the factor really is used)."""
@@ -503,7 +512,7 @@ def _many_seqs(n, seed):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_batches_larger_than_one_sequence_table(oracle, dtype):
+def test_batches_larger_than_one_sequence_table(oracle, dtype, prefill_kernel):
     """130 packed sequences: the host hands the sequence table to the kernels in pieces of 48, so
     work-list offsets, compact question rows and RoPE rows cross piece boundaries."""
     seqs = _many_seqs(130, 5)
@@ -565,7 +574,7 @@ def _random_case(rng):
 
 
 @pytest.mark.parametrize("dtype,seed", [("bf16", 101), ("bf16", 102), ("bf16", 103), ("f32", 104), ("bf16", 105), ("bf16", 106), ("f32", 107), ("bf16", 108)])
-def test_seeded_sweep_of_small_layouts(oracle, dtype, seed):
+def test_seeded_sweep_of_small_layouts(oracle, dtype, seed, prefill_kernel):
     """Twelve random small layouts per seed (ragged tiles, 1-token blocks, missing regions, GQA widths
     1/2/4/7, explicit head maps, split counts 0-5) through all three calls, every row against the
     oracle; the bf16 cases also through the calls with RoPE folded in."""
@@ -604,7 +613,7 @@ STREAM_CASES = [
 
 
 @pytest.mark.parametrize("name,dtype,Hq,Hkv,D,seqs", STREAM_CASES, ids=[c[0] for c in STREAM_CASES])
-def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(oracle, name, dtype, Hq, Hkv, D, seqs):
+def test_blocks_arriving_in_pieces_reproduce_the_one_shot_prefill(oracle, name, dtype, Hq, Hkv, D, seqs, prefill_kernel):
     """Sink + first blocks, then the remaining blocks two at a time: every call writes exactly its
     rows, the pieces add up to pevlm_block_prefill_attn bit for bit, and equal the oracle's rows."""
     w = W.Workload(name, 17, dtype, Hq, Hkv, D, 1.0e6, seqs, 0.5 if dtype == "bf16" else 1.0)
@@ -717,7 +726,7 @@ def _guards_intact(buf, nbytes, guard=4096):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_nothing_is_written_outside_out_lse_and_the_workspaces(dtype):
+def test_nothing_is_written_outside_out_lse_and_the_workspaces(dtype, prefill_kernel):
     """out, lse and both workspaces sit between guard bands (workspaces sized exactly as the
     *_workspace_bytes queries say); after all calls every guard byte still holds its pattern."""
     seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)]
@@ -754,7 +763,7 @@ def test_nothing_is_written_outside_out_lse_and_the_workspaces(dtype):
 
 
 # ------------------------------------------------------------------------------------ graph capture
-def test_calls_can_be_captured_in_a_graph_and_replayed():
+def test_calls_can_be_captured_in_a_graph_and_replayed(prefill_kernel):
     """The library neither allocates nor synchronises nor clears memory with memset nodes, so the
     three calls can be recorded into a HIP graph.  Replays (with eager work and synchronisation in
     between, on fresh inputs each time) must reproduce the eager result bit for bit."""

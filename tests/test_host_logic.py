@@ -104,7 +104,6 @@ STREAM_HEADS = [(4, 2, None), (7, 1, None), (8, 2, [1, 0, 0, 1, 1, 0, 1, 0]), (3
 def test_stream_items_expand_to_oracle_mask(oracle, seqs, Hq, Hkv, hmap):
     lay = P.Layout.from_seqs(seqs)
     heads = P.Heads(Hq, Hkv, 128, "bf16", hmap)
-    assert P.pevlm_prefill_uses_stream_kernel(heads)
     T = lay.total_tokens
     olay = oracle.Layout(lay.cu, lay.s, lay.b, lay.c, lay.q)
     want = oracle.mask_matrix(olay)
@@ -133,12 +132,25 @@ def test_stream_items_of_a_block_selection_and_unequal_groups():
     assert len(sel) > 0 and all(fullmap[key(it)] == bytes(it) for it in sel)
     rows = sorted({r for it in sel for sl in it.slot if sl.q_rows for r in range(sl.q_start, sl.q_start + sl.q_rows)})
     assert rows == list(range(70 + 100, 70 + 350)) + list(range(429, 429 + 66))
-    # unequal groups per KV head: the one-item kernel is used instead
+    # unequal groups per KV head, fp32 tensors, short lists: the one-item kernel is used instead
     uneven = P.Heads(4, 2, 128, "bf16", [0, 0, 0, 1])
-    assert not P.pevlm_prefill_uses_stream_kernel(uneven)
-    assert not P.pevlm_prefill_uses_stream_kernel(P.Heads(4, 2, 64, "f32"))
     with pytest.raises(P.PevlmError):
         P.pevlm_prefill_stream_items_host(lay, uneven)
+    big = P.Layout.from_seqs([(256, 1024, 65536, 128)])
+    prev = P.pevlm_set_prefill_kernel("auto")
+    try:
+        assert P.pevlm_prefill_uses_stream_kernel(big, P.Heads(28, 4, 128, "bf16"))
+        assert not P.pevlm_prefill_uses_stream_kernel(big, P.Heads(28, 4, 128, "f32"))
+        assert not P.pevlm_prefill_uses_stream_kernel(big, P.Heads(4, 2, 128, "bf16", [0, 0, 0, 1]))
+        assert not P.pevlm_prefill_uses_stream_kernel(lay, heads)  # a few dozen items for 256 compute units
+        assert P.pevlm_set_prefill_kernel("stream") == 0
+        assert P.pevlm_prefill_uses_stream_kernel(lay, heads) and not P.pevlm_prefill_uses_stream_kernel(lay, uneven)
+        assert P.pevlm_set_prefill_kernel("classic") == 2
+        assert not P.pevlm_prefill_uses_stream_kernel(big, P.Heads(28, 4, 128, "bf16"))
+        with pytest.raises(P.PevlmError):
+            P.pevlm_set_prefill_kernel(7)
+    finally:
+        P.pevlm_set_prefill_kernel(prev)
 
 
 @pytest.mark.parametrize("seqs", LAYOUTS)
