@@ -43,4 +43,12 @@ from .binding import (  # noqa: F401
     pevlm_version,
     pevlm_visible_pairs,
 )
-from .cost_model import choose_block_len, predict_block_prefill_ms, prefill_work, useful_flops  # noqa: F401
+from .cost_model import (  # noqa: F401
+    choose_block_len,
+    choose_sink_and_block,
+    predict_block_prefill_ms,
+    prefill_work,
+    stream_work,
+    useful_flops,
+    video_layout,
+)

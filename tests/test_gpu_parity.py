@@ -713,6 +713,51 @@ def test_windowed_question_full_size_c3(oracle):
     check_bf16(to_host_f32(out[torch.from_numpy(qrows).to(DEV)]), want, "c3/window16")
 
 
+# ------------------------------------------------------------------------------------ time model
+def test_time_model_against_fresh_measurements():
+    """The block-prefill time model behind the sink / block-size chooser, against launches timed here.
+    Boxes differ by several per cent in sustained clock, so the check is in two parts: every predicted
+    time within 20 % of the measured one, and -- with the box's speed taken out through one reference
+    point -- every predicted ratio to the reference within 12 % of the measured ratio."""
+    from paper_2506_19651_amd.cost_model import choose_sink_and_block, predict_block_prefill_ms, video_layout
+    heads = P.Heads(28, 4, 128, "bf16")
+    grid = [(1, 4), (2, 8), (4, 2), (4, 16), (8, 8)]  # (sink frames, block frames); the first is the reference
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    meas, pred = [], []
+    for sf, bf in grid:
+        S, B, C, Q = video_layout(0, 256, 256, 128, sf, bf)
+        lay = P.Layout.from_seqs([(S, B, C, Q)])
+        T = S + C + Q
+        g = torch.Generator(device=DEV).manual_seed(5)
+        q = (torch.randn(T, 28, 128, device=DEV, generator=g) * 0.5).bfloat16()
+        k = (torch.randn(T, 4, 128, device=DEV, generator=g) * 0.5).bfloat16()
+        v = (torch.randn(T, 4, 128, device=DEV, generator=g) * 0.5).bfloat16()
+        out = torch.empty_like(q)
+        ws = torch.empty(P.pevlm_block_prefill_workspace_bytes(lay, heads), dtype=torch.uint8, device=DEV)
+        for _ in range(3):
+            P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, workspace=ws)
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(8):
+                P.pevlm_block_prefill_attn(q, k, v, out, lay, heads, workspace=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / 8)
+        meas.append(sorted(ts)[1])
+        pred.append(predict_block_prefill_ms(lay, heads, n_cu))
+        print(f"[time model] sink {sf} frames, block {bf} frames: measured {meas[-1]:.3f} ms, predicted {pred[-1]:.3f} ms", flush=True)
+    for m, p_ in zip(meas, pred):
+        assert abs(p_ / m - 1.0) <= 0.20, (meas, pred)
+        assert abs((p_ / pred[0]) / (m / meas[0]) - 1.0) <= 0.12, (meas, pred)
+    # the chooser's pick under a cap set between two measured points really fits that cap here
+    cap = 0.5 * (sorted(meas)[1] + sorted(meas)[2])
+    best, _table = choose_sink_and_block(0, 256, 256, 128, heads, [sf for sf, _ in grid], [bf for _, bf in grid], cap, n_cu)
+    assert best is not None and best[2] <= cap
+
+
 # ------------------------------------------------------------------------------------ guard bands
 def _guarded(nbytes, guard=4096):
     """A device byte range of exactly `nbytes` with `guard` bytes of a known pattern on both sides."""

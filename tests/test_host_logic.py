@@ -329,24 +329,46 @@ def test_workspace_sizes_cover_items_and_partials():
         assert P.pevlm_query_workspace_bytes(lay, heads, ns) >= need
 
 
-def test_time_model_tracks_measured_runs_and_block_length_choice():
-    import workloads as W
-    from paper_2506_19651_amd.cost_model import choose_block_len, predict_block_prefill_ms, prefill_work
-    for line in open(os.path.join(ROOT, "tests", "golden", "measured_block_prefill_ms.txt")):
-        if not line.strip() or line.startswith("#"):
-            continue
-        name, ms = line.split()
-        w = W.CONFIGS[name]
-        lay, heads = P.Layout.from_seqs(w.seqs), P.Heads(w.n_q_heads, w.n_kv_heads, w.head_dim, "bf16")
-        pred = predict_block_prefill_ms(lay, heads)
-        assert abs(pred / float(ms) - 1.0) <= 0.12, (name, pred, ms)
-    # workgroup count of the headline config: 514 items x 28 heads
-    w = W.CONFIGS["c3"]
-    assert prefill_work(P.Layout.from_seqs(w.seqs), P.Heads(28, 4, 128, "bf16"))[0] == 514 * 28
-    # block-length sweep of the 100K-token configuration (2/4/8/16 frames of 196 tokens) under a cap
-    heads = P.Heads(32, 8, 128, "bf16")
-    pick = lambda cap: choose_block_len(392, 100352, 256, heads, [392, 784, 1568, 3136], cap)
-    assert pick(1.0) is None
-    assert pick(1.8)[0] == 784 and pick(2.5)[0] == 1568 and pick(10.0)[0] == 3136
-    assert predict_block_prefill_ms(P.Layout.from_seqs([(392, 392, 100352, 256)]), heads) < \
-        predict_block_prefill_ms(P.Layout.from_seqs([(392, 3136, 100352, 256)]), heads)
+def test_time_model_tracks_measured_runs_and_sink_block_choice():
+    """The model against the measured grid kept under profiles/ (product timings, not oracle values),
+    then the choosers: feasibility under a cap, preference for the most visible pairs."""
+    from paper_2506_19651_amd.cost_model import (choose_block_len, choose_sink_and_block, predict_block_prefill_ms,
+                                                 prefill_work, stream_work, video_layout)
+    prev = P.pevlm_set_prefill_kernel("auto")
+    try:
+        n = 0
+        for line in open(os.path.join(ROOT, "profiles", "block_prefill_sweep.md")):
+            f = line.split()
+            if len(f) != 7 or f[0] not in ("q7b", "g32"):
+                continue
+            S, B, C, Q, ms, stream = int(f[1]), int(f[2]), int(f[3]), int(f[4]), float(f[5]), int(f[6])
+            heads = P.Heads(28, 4, 128, "bf16") if f[0] == "q7b" else P.Heads(32, 8, 128, "bf16")
+            lay = P.Layout.from_seqs([(S, B, C, Q)])
+            assert int(P.pevlm_prefill_uses_stream_kernel(lay, heads)) == stream
+            pred = predict_block_prefill_ms(lay, heads)
+            assert abs(pred / ms - 1.0) <= 0.12, (line, pred)
+            n += 1
+        assert n >= 30
+        # work of the headline config under both kernels
+        lay3, h3 = P.Layout.from_seqs([(256, 1024, 65536, 128)]), P.Heads(28, 4, 128, "bf16")
+        assert prefill_work(lay3, h3)[0] == 514 * 28
+        cnt, til = stream_work(lay3, h3)
+        assert len(cnt) == 256 and cnt.sum() == (7 + 64 * 28) * 4 and 28 <= cnt.min() <= cnt.max() <= 29
+        # one knob: block-length sweep of the 100K-token configuration (2/4/8/16 frames of 196 tokens)
+        heads = P.Heads(32, 8, 128, "bf16")
+        pick = lambda cap: choose_block_len(392, 100352, 256, heads, [392, 784, 1568, 3136], cap)
+        assert pick(1.0) is None
+        assert pick(1.8)[0] == 784 and pick(2.5)[0] == 1568 and pick(10.0)[0] == 3136
+        # both knobs: 256 frames of 256 tokens behind a 64-token prefix
+        assert video_layout(64, 256, 256, 128, 2, 4) == (64 + 512, 1024, 254 * 256, 128)
+        best, table = choose_sink_and_block(64, 256, 256, 128, h3, [1, 2, 4, 8, 16], [2, 4, 8, 16], 1.5)
+        assert len(table) == 20 and best is not None and best[2] <= 1.5
+        feasible = [r for r in table if r[2] <= 1.5]
+        assert best[3] == max(r[3] for r in feasible)            # most visible pairs within the cap
+        assert any(r[2] > 1.5 and r[3] > best[3] for r in table)  # and something better was too slow
+        assert choose_sink_and_block(64, 256, 256, 128, h3, [1, 2], [2, 4], 0.2)[0] is None
+        # the cost grows with either knob (Eq. 7 and Eq. 8 are quadratic in S and B)
+        t = {(r[0], r[1]): r[2] for r in table}
+        assert t[(1, 2)] < t[(1, 16)] and t[(1, 2)] < t[(16, 2)] and t[(4, 4)] < t[(8, 8)]
+    finally:
+        P.pevlm_set_prefill_kernel(prev)
