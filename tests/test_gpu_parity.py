@@ -148,6 +148,31 @@ def test_bf16_hard_softmax_cases(oracle, name, extra, seqs, splits, prefill_kern
     assert np.all(lse_err <= 2e-2 + 1e-4 * np.abs(want_lse))
 
 
+TAILS = [(128, 1), (128, 31), (128, 32), (128, 33), (128, 63), (64, 8), (64, 40)]
+
+
+@pytest.mark.parametrize("D,tail", TAILS, ids=[f"D{d}_tail{t}" for d, t in TAILS])
+def test_bf16_sink_that_does_not_fill_a_key_tile(oracle, D, tail, prefill_kernel):
+    """Sinks of 64 n + tail keys (the last key tile of the sink is ragged, the block's own keys start in
+    a fresh tile): blocks shorter and longer than a tile, a sink smaller than a tile, several
+    sequences.  Oracle fed with the GPU's rotated bf16 Q/K; exactness of the mask is covered by the
+    zero-weight test below."""
+    seqs = [(64 + tail, 150, 700, 20), (tail, 40, 130, 0), (128 + tail, 64 - tail, 300, 7)]
+    w = W.Workload(f"tail{tail}", 40 + tail, "bf16", 4, 2, D, 1.0e6, seqs, 0.5)
+    data = W.generate(w)
+    r = run_path(w, data, num_splits=2, want_lse=True)
+    olay = oracle_layout(oracle, w)
+    q_rot, k_rot = to_host_f32(r["q_rot"]).astype(np.float64), to_host_f32(r["k_rot"]).astype(np.float64)
+    want, want_lse = oracle.attn(q_rot, k_rot, data["v"], olay)
+    got = to_host_f32(r["out"])
+    st = error_stats(got, want)
+    print(f"[tail {tail} D {D}] max_abs={st['max_abs']:.3e} mean_abs={st['mean_abs']:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert st["max_abs"] <= BF16_MAX and st["mean_abs"] <= BF16_MEAN, st
+    lse_err = np.abs(to_host_f32(r["lse"]) - want_lse)
+    assert np.all(lse_err <= 2e-2 + 1e-4 * np.abs(want_lse))
+
+
 def prefill_list_on_device(ws, lay, heads):
     """True if the work list the block-prefill call left in its workspace equals the host enumeration
     (stream items for the streaming bf16 kernel, plain work items otherwise)."""
