@@ -265,6 +265,46 @@ int64_t pevlm_prefill_stream_items_host(const pevlm_layout *layout, const pevlm_
                                         const int32_t *num_blocks, int32_t with_sink, pevlm_stream_item *items,
                                         int64_t capacity);
 
+/* ---- fp8 variant of the block-prefill call (an extension of Eq. 3-4 to 8-bit operands; bf16 in, bf16 out)
+ *
+ * pevlm_block_prefill_attn_fp8 computes the same rows as pevlm_block_prefill_attn from E4M3 copies
+ * of Q, K and V (OCP 8-bit floating point: 4 exponent bits with bias 7, 3 mantissa bits, largest
+ * value 448, no infinities) on the fp8 matrix cores, with fp32 accumulation and fp32 softmax; the
+ * attention weights are rounded to E4M3 as well.  It runs in two stages, selected by `stages`
+ * (0 = both): PEVLM_FP8_QUANTISE writes the work lists and the codes into the workspace,
+ * PEVLM_FP8_ATTEND computes `out` (and `lse`) from a workspace a QUANTISE stage has filled for the
+ * same layout, heads and tensors (q, k, v are not read by it).
+ *
+ * A tensor is stored as codes times a power-of-two scale 2^e, e the smallest integer with
+ * amax * 2^-e <= 448 (amax: the largest magnitude the scale covers; e = 0 if that is 0; e within
+ * [-100, 100]); codes are rounded to nearest, ties to even.  Q has one scale per (token, query
+ * head), K and V one per KV head over all tokens of the call.  Inputs must be finite.
+ *
+ * Workspace (DEVICE, 256-byte aligned, pevlm_block_prefill_fp8_workspace_bytes; byte offsets of its
+ * parts from pevlm_block_prefill_fp8_plan):
+ *   q_codes   [T][Hq][D] codes;  q_scales [T][Hq] fp32 scales (2^e)
+ *   kv_amax   [2][Hkv] fp32: largest magnitude of K, then of V, per KV head
+ *   key_tiles n_key_tiles pevlm_work_item: (q_start, q_rows) = the token rows of key tile i; the
+ *             tiles are the 64-row tiles of pevlm_prefill_worklist_host(layout, 64, ...)
+ *   k_tiles   [key tile][Hkv][64 rows][D] codes, rows past q_rows zero; the 16-byte chunk c of row r
+ *             is stored at chunk position c ^ ((r / (256 / D)) % (D / 16)) of the row
+ *   v_tiles   [key tile][Hkv][D rows][64] codes: row d, byte j holds key
+ *             ((j % 32) / 16) * 32 + ((j % 16) / 4) * 8 + (j / 32) * 4 + j % 4 of the tile; the 16-byte
+ *             chunk c of row d is stored at chunk position c ^ ((d / 4) % 4)
+ * head_dim 64 or 128, dtype PEVLM_BF16 (else PEVLM_ERR_UNSUPPORTED).  Other arguments, ownership
+ * and error behaviour as pevlm_block_prefill_attn. */
+enum { PEVLM_FP8_QUANTISE = 1, PEVLM_FP8_ATTEND = 2 };
+typedef struct {
+    int64_t n_items, n_key_tiles;
+    size_t items, key_tiles, kv_amax, q_scales, q_codes, k_tiles, v_tiles; /* byte offsets into the workspace */
+    size_t total;                                                        /* = pevlm_block_prefill_fp8_workspace_bytes */
+} pevlm_fp8_plan;
+pevlm_status pevlm_block_prefill_fp8_plan(const pevlm_layout *layout, const pevlm_heads *heads, pevlm_fp8_plan *plan);
+size_t pevlm_block_prefill_fp8_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads);
+pevlm_status pevlm_block_prefill_attn_fp8(const void *q, const void *k, const void *v, void *out, float *lse,
+                                          const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
+                                          size_t workspace_bytes, int32_t stages, void *stream);
+
 /* Query rows per work item the kernels selected by `heads` use for the block-prefill call and for
  * the question call (-1 for an invalid descriptor). */
 int32_t pevlm_prefill_tile_rows(const pevlm_heads *heads);

@@ -50,6 +50,11 @@ class StreamItem(ctypes.Structure):
                                               "n_full_tiles", "n_tiles", "seq")] + [("slot", _StreamSlot * 8)]
 
 
+class Fp8Plan(ctypes.Structure):
+    _fields_ = [("n_items", ctypes.c_int64), ("n_key_tiles", ctypes.c_int64)] + \
+               [(n, ctypes.c_size_t) for n in ("items", "key_tiles", "kv_amax", "q_scales", "q_codes", "k_tiles", "v_tiles", "total")]
+
+
 _lib = None
 
 
@@ -103,6 +108,12 @@ def load_library():
                                                        ctypes.c_size_t, vp]
         lib.pevlm_query_attn_mrope.restype = ctypes.c_int
         lib.pevlm_query_attn_mrope.argtypes = [vp, vp, vp, vp, f32p, LP, HP, i32, ctypes.c_double, vp, i32p, vp, ctypes.c_size_t, vp]
+        lib.pevlm_block_prefill_fp8_plan.restype = ctypes.c_int
+        lib.pevlm_block_prefill_fp8_plan.argtypes = [LP, HP, ctypes.POINTER(Fp8Plan)]
+        lib.pevlm_block_prefill_fp8_workspace_bytes.restype = ctypes.c_size_t
+        lib.pevlm_block_prefill_fp8_workspace_bytes.argtypes = [LP, HP]
+        lib.pevlm_block_prefill_attn_fp8.restype = ctypes.c_int
+        lib.pevlm_block_prefill_attn_fp8.argtypes = [vp, vp, vp, vp, f32p, LP, HP, vp, ctypes.c_size_t, i32, vp]
         lib.pevlm_last_error.restype = ctypes.c_char_p
         lib.pevlm_version.restype = i32
         lib.pevlm_prefill_tile_rows.restype = i32
@@ -307,6 +318,29 @@ def pevlm_block_prefill_attn(q, k, v, out, layout: Layout, heads: Heads, lse=Non
     _check(load_library().pevlm_block_prefill_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
                                                    heads.ref(), _ptr(workspace), workspace.numel(),
                                                    _stream_ptr(stream)))
+    return workspace
+
+
+FP8_QUANTISE, FP8_ATTEND = 1, 2
+
+
+def pevlm_block_prefill_fp8_plan(layout: Layout, heads: Heads) -> Fp8Plan:
+    plan = Fp8Plan()
+    _check(load_library().pevlm_block_prefill_fp8_plan(layout.ref(), heads.ref(), ctypes.byref(plan)))
+    return plan
+
+
+def pevlm_block_prefill_fp8_workspace_bytes(layout: Layout, heads: Heads) -> int:
+    return int(load_library().pevlm_block_prefill_fp8_workspace_bytes(layout.ref(), heads.ref()))
+
+
+def pevlm_block_prefill_attn_fp8(q, k, v, out, layout: Layout, heads: Heads, lse=None, workspace=None, stages: int = 0,
+                                 stream=None):
+    if workspace is None:
+        workspace = _workspace(pevlm_block_prefill_fp8_workspace_bytes(layout, heads), q)
+    _check(load_library().pevlm_block_prefill_attn_fp8(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), layout.ref(),
+                                                       heads.ref(), _ptr(workspace), workspace.numel(), int(stages),
+                                                       _stream_ptr(stream)))
     return workspace
 
 

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpevlm.so")
-SOURCES = ["api.hip", "worklist_merge.hip", "rope.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_stream.hip", "probe.hip"]
+SOURCES = ["api.hip", "worklist_merge.hip", "rope.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_stream.hip", "attn_fp8.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

@@ -583,6 +583,120 @@ pevlm_status pevlm_block_prefill_attn_rope(const void *q, void *k, const void *v
                         k_is_rotated == 0);
 }
 
+// ---- fp8 variant of the block-prefill call
+static pevlm_status fp8_plan(const pevlm_layout *layout, const pevlm_heads *heads, pevlm_fp8_plan *plan)
+{
+    pevlm_status st = check_layout(layout);
+    if (st != PEVLM_OK) return st;
+    st = check_heads(heads, nullptr);
+    if (st != PEVLM_OK) return st;
+    if (heads->dtype != PEVLM_BF16) return fail(PEVLM_ERR_UNSUPPORTED, "the fp8 variant takes bf16 tensors");
+    const int64_t T = layout->cu_seqlens[layout->num_seqs];
+    const int64_t n_items = count_prefill_items(layout, kFp8TileRows), n_key_tiles = count_prefill_items(layout, kKeyTile);
+    if (n_items * heads->n_q_heads > 0x3fffffff || n_key_tiles > 0x3fffffff) return fail(PEVLM_ERR_UNSUPPORTED, "too many work items");
+    const size_t tile_bytes = (size_t)kKeyTile * heads->head_dim;
+    size_t off = 0;
+    plan->n_items = n_items;
+    plan->n_key_tiles = n_key_tiles;
+    plan->items = off;     off += align256((size_t)n_items * sizeof(Fp8Item));
+    plan->key_tiles = off; off += align256((size_t)n_key_tiles * sizeof(pevlm_work_item));
+    plan->kv_amax = off;   off += align256((size_t)2 * heads->n_kv_heads * sizeof(uint32_t));
+    plan->q_scales = off;  off += align256((size_t)T * heads->n_q_heads * sizeof(float));
+    plan->q_codes = off;   off += align256((size_t)T * heads->n_q_heads * heads->head_dim);
+    plan->k_tiles = off;   off += align256((size_t)n_key_tiles * heads->n_kv_heads * tile_bytes);
+    plan->v_tiles = off;   off += align256((size_t)n_key_tiles * heads->n_kv_heads * tile_bytes);
+    plan->total = off + 256;
+    return PEVLM_OK;
+}
+
+pevlm_status pevlm_block_prefill_fp8_plan(const pevlm_layout *layout, const pevlm_heads *heads, pevlm_fp8_plan *plan)
+{
+    if (!plan) return fail(PEVLM_ERR_INVALID_ARG, "plan must not be NULL");
+    return fp8_plan(layout, heads, plan);
+}
+
+size_t pevlm_block_prefill_fp8_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads)
+{
+    pevlm_fp8_plan plan;
+    return fp8_plan(layout, heads, &plan) == PEVLM_OK ? plan.total : 0;
+}
+
+pevlm_status pevlm_block_prefill_attn_fp8(const void *q, const void *k, const void *v, void *out, float *lse,
+                                          const pevlm_layout *layout, const pevlm_heads *heads, void *workspace,
+                                          size_t workspace_bytes, int32_t stages, void *stream)
+{
+    pevlm_fp8_plan plan;
+    pevlm_status st = fp8_plan(layout, heads, &plan);
+    if (st != PEVLM_OK) return st;
+    Fp8Params p;
+    memset(&p, 0, sizeof p);
+    st = check_heads(heads, &p.heads);
+    if (st != PEVLM_OK) return st;
+    if (stages == 0) stages = PEVLM_FP8_QUANTISE | PEVLM_FP8_ATTEND;
+    if (stages & ~(PEVLM_FP8_QUANTISE | PEVLM_FP8_ATTEND)) return fail(PEVLM_ERR_INVALID_ARG, "unknown stage bits %d", stages);
+    if (!q || !k || !v || !out) return fail(PEVLM_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && ((uintptr_t)lse & 3)))
+        return fail(PEVLM_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (plan.n_items == 0) return PEVLM_OK;
+    if (!workspace || workspace_bytes < plan.total - 256 || ((uintptr_t)workspace & 255))
+        return fail(PEVLM_ERR_WORKSPACE_TOO_SMALL, "fp8 prefill workspace needs %zu bytes, 256-byte aligned (got %zu)", plan.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    hipStream_t hs = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    Fp8Item *items = (Fp8Item *)(ws + plan.items);
+    pevlm_work_item *key_tiles = (pevlm_work_item *)(ws + plan.key_tiles);
+    const int64_t T = layout->cu_seqlens[layout->num_seqs];
+    if (stages & PEVLM_FP8_QUANTISE) {
+        // both lists (they depend on the layout only), then the codes
+        int32_t item_offset = 0, tile_offset = 0;
+        for (int32_t s0 = 0; s0 < layout->num_seqs; s0 += kMaxSeqsPerLaunch) {
+            SeqTable tab;
+            Fp8TileBases bases;
+            const int32_t n = std::min(kMaxSeqsPerLaunch, layout->num_seqs - s0);
+            fill_table(layout, s0, n, nullptr, &tab);
+            bases.base[0] = tile_offset;
+            for (int32_t i = 0; i < n; ++i) {
+                tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], kKeyTile);
+                bases.base[i + 1] = tile_offset + tab.item_base[i + 1];
+            }
+            if (tab.item_base[n] > 0) {
+                hipError_t e = launch_build_prefill_items(tab, kKeyTile, key_tiles, tile_offset, hs);
+                if (e != hipSuccess) return hip_fail(e, "key-tile list launch");
+            }
+            tile_offset += tab.item_base[n];
+            for (int32_t i = 0; i < n; ++i)
+                tab.item_base[i + 1] = tab.item_base[i] + prefill_items_of_seq(tab.sink[i], tab.block[i], tab.ctx[i], kFp8TileRows);
+            if (tab.item_base[n] > 0) {
+                hipError_t e = launch_build_fp8_items(tab, bases, items, item_offset, hs);
+                if (e != hipSuccess) return hip_fail(e, "fp8 work-list launch");
+            }
+            item_offset += tab.item_base[n];
+        }
+        hipError_t e = launch_fp8_quantise(q, k, v, T, heads->n_q_heads, heads->n_kv_heads, heads->head_dim, key_tiles,
+                                           (int32_t)plan.n_key_tiles, (uint32_t *)(ws + plan.kv_amax), (float *)(ws + plan.q_scales),
+                                           (uint8_t *)(ws + plan.q_codes), (uint8_t *)(ws + plan.k_tiles),
+                                           (uint8_t *)(ws + plan.v_tiles), compute_units(), hs);
+        if (e != hipSuccess) return hip_fail(e, "fp8 quantise launch");
+    }
+    if (stages & PEVLM_FP8_ATTEND) {
+        p.q_codes = (const uint8_t *)(ws + plan.q_codes);
+        p.q_scales = (const float *)(ws + plan.q_scales);
+        p.k_tiles = (const uint8_t *)(ws + plan.k_tiles);
+        p.v_tiles = (const uint8_t *)(ws + plan.v_tiles);
+        p.kv_amax = (const uint32_t *)(ws + plan.kv_amax);
+        p.out = out;
+        p.lse = lse;
+        p.items = items;
+        p.n_items = (int32_t)plan.n_items;
+        p.n_q_heads = heads->n_q_heads;
+        p.n_kv_heads = heads->n_kv_heads;
+        p.scale = scale_of(heads);
+        hipError_t e = launch_attn_fp8(p, heads->head_dim, hs);
+        if (e != hipSuccess) return hip_fail(e, "fp8 block-prefill launch");
+    }
+    return PEVLM_OK;
+}
+
 size_t pevlm_query_workspace_bytes(const pevlm_layout *layout, const pevlm_heads *heads, int32_t num_splits)
 {
     if (check_layout(layout) != PEVLM_OK || check_heads(heads, nullptr) != PEVLM_OK) return 0;

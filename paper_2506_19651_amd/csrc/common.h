@@ -312,6 +312,31 @@ struct StreamParams {
     float scale;
 };
 
+// fp8 variant of the block-prefill call: 128 query rows of one region; its key tiles are tiles
+// full_tile0 .. of the sink and diag_tile0 .. of its own region in the tiled E4M3 copies of K and V
+struct Fp8Item {
+    int32_t q_start, q_rows;
+    int32_t full_start, full_len;
+    int32_t diag_start, diag_len;
+    int32_t full_tile0, diag_tile0;
+};
+struct Fp8TileBases {
+    int32_t base[kMaxSeqsPerLaunch + 1];  // first key tile of each sequence of the chunk (batch-absolute)
+};
+struct Fp8Params {
+    const uint8_t *q_codes;   // [T][Hq][D]
+    const float *q_scales;    // [T][Hq]
+    const uint8_t *k_tiles, *v_tiles;  // [key tile][Hkv][64 * D]
+    const uint32_t *kv_amax;  // [2][Hkv] bit patterns of the largest magnitudes of K and V per head
+    void *out;                // [T][Hq][D] bf16
+    float *lse;
+    const Fp8Item *items;
+    int32_t n_items;
+    int32_t n_q_heads, n_kv_heads;
+    float scale;
+    HeadTable heads;
+};
+
 struct MergeParams {
     const float *part_acc, *part_ml;
     const int32_t *qrow_of_compact;  // [total_q_rows] packed row of each compact question row
@@ -343,6 +368,12 @@ hipError_t launch_build_stream_items(const SeqTable &tab, int32_t G, int32_t Hkv
                                      pevlm_stream_item *items, int32_t item_offset, hipStream_t stream);
 // block-prefill rows of bf16 tensors from a stream-item list; workgroups = compute units (8 wavefronts each)
 hipError_t launch_attn_bf16_stream(const StreamParams &p, int32_t D, int32_t compute_units, hipStream_t stream);
+hipError_t launch_build_fp8_items(const SeqTable &tab, const Fp8TileBases &bases, Fp8Item *items, int32_t item_offset, hipStream_t stream);
+// bf16 Q, K, V -> E4M3 codes and scales (key_tiles: the prefill items of 64 rows, one per K/V tile)
+hipError_t launch_fp8_quantise(const void *q, const void *k, const void *v, int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                               const pevlm_work_item *key_tiles, int32_t n_key_tiles, uint32_t *kv_amax, float *q_scales,
+                               uint8_t *q_codes, uint8_t *k_tiles, uint8_t *v_tiles, int32_t compute_units, hipStream_t stream);
+hipError_t launch_attn_fp8(const Fp8Params &p, int32_t D, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);  // p.rope_tab selects the fused variant
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);
@@ -351,6 +382,7 @@ hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStrea
 
 constexpr int32_t kTileRowsF32 = 16;   // query rows per work item of the fp32 kernels
 constexpr int32_t kTileRowsBf16 = 128; // query rows per work item of the bf16 MFMA kernels
-constexpr int32_t kKeyTile = 64;       // keys staged per step by the bf16 kernels
+constexpr int32_t kKeyTile = 64;       // keys staged per step by the bf16 and fp8 kernels
+constexpr int32_t kFp8TileRows = 128;  // query rows per work item of the fp8 kernel
 
 }  // namespace pevlm
