@@ -23,9 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+MFMA_FP8_PEAK_TFLOPS = 5000.0   # ... dense fp8
 # HBM bytes per block-prefill launch from the FETCH_SIZE / WRITE_SIZE passes recorded in
 # profiles/attn_bf16_prefill_c3_counters.md (scaled by the same counters on a 1 GiB device copy)
-MEASURED_PREFILL_TRAFFIC_BYTES = {"c3": 1.095e9}
+MEASURED_PREFILL_TRAFFIC_BYTES = {}
 HBM_PEAK_GBS = 8000.0
 
 
@@ -115,6 +116,9 @@ def main():
     ms_rope, ms_prefill, ms_query = float(t_rope.mean()), float(t_prefill.mean()), float(t_query.mean())
 
     f_prefill, f_query = P.useful_flops(lay, heads)
+    # which of the two block-prefill kernels the library ran for this layout (its own per-call choice)
+    prefill_kernel_name = (f"attn_bf16_stream_kernel<{w.head_dim}>" if P.pevlm_prefill_uses_stream_kernel(lay, heads)
+                           else f"attn_bf16_kernel<{w.head_dim},false,false>")
     T = w.total_tokens
     rope_bytes = 2 * T * (w.n_q_heads + w.n_kv_heads) * w.head_dim * 2
     kv_bytes = 2 * T * w.n_kv_heads * w.head_dim * 2
@@ -148,13 +152,13 @@ def main():
         "rope_gbs": round(rope_bytes / (ms_rope * 1e-3) / 1e9, 1),
         "query_kv_gbs": round(kv_bytes / (ms_query * 1e-3) / 1e9, 1),
         "roofline": {
-            "kernel": "attn_bf16_kernel<128,false,false> (block-prefill)",
+            "kernel": prefill_kernel_name + " (block-prefill)",
             "bound": "mfma",
             "achieved": round(f_prefill / (ms_prefill * 1e-3) / 1e12, 2),
             "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(f_prefill / (ms_prefill * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(args.workload),
+            "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get((args.workload, prefill_kernel_name)),
         },
         "paper_context": "paper reports up to 7.47x attention speedup on one NVIDIA H20-96G (bf16, ~100k tokens)",
     }
@@ -200,6 +204,41 @@ def main():
             "ms_query_attn": round(float(np.mean([e[2].elapsed_time(e[3]) for e in events_f])), 4),
             "bit_identical_to_three_call_path": fused_matches,
         }
+
+    if not args.no_extras:
+        # fp8 (E4M3) variant of the block-prefill call: quantise stage (bf16 -> codes, K/V re-tiled) and
+        # attention stage timed separately and together; judged against the fp8 matrix peak
+        ws_8 = torch.empty(P.pevlm_block_prefill_fp8_workspace_bytes(lay, heads), dtype=torch.uint8, device=dev)
+        out_8 = torch.zeros_like(q)
+
+        def timed_stage(stages):
+            P.pevlm_block_prefill_attn_fp8(q, k, v, out_8, lay, heads, workspace=ws_8, stages=stages, stream=stream)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(max(5, args.steps // 2)):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                P.pevlm_block_prefill_attn_fp8(q, k, v, out_8, lay, heads, workspace=ws_8, stages=stages, stream=stream)
+                b.record(stream)
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return float(np.mean(ts))
+
+        ms_8q, ms_8a, ms_8 = timed_stage(P.FP8_QUANTISE), timed_stage(P.FP8_ATTEND), timed_stage(0)
+        a_ = w.layout_arrays()
+        pre_rows = torch.cat([torch.arange(int(c0), int(c0) + s_ + c_, device=dev)
+                              for c0, (s_, _b, c_, _q) in zip(a_["cu_seqlens"], w.seqs)])
+        diff8 = (out_8[pre_rows].float() - first_out[pre_rows].float()).abs()
+        result["fp8_block_prefill"] = {
+            "ms_quantise": round(ms_8q, 4), "ms_attend": round(ms_8a, 4), "ms_both": round(ms_8, 4),
+            "attend_useful_tflops": round(f_prefill / (ms_8a * 1e-3) / 1e12, 2),
+            "roofline": {"kernel": f"attn_fp8_kernel<{w.head_dim}>", "bound": "mfma", "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "achieved": round(f_prefill / (ms_8a * 1e-3) / 1e12, 2),
+                         "frac": round(f_prefill / (ms_8a * 1e-3) / 1e12 / MFMA_FP8_PEAK_TFLOPS, 4)},
+            "speedup_of_attend_over_bf16_kernel": round(ms_prefill / ms_8a, 3),
+            "max_abs_diff_to_bf16_path": float(diff8.max()), "mean_abs_diff_to_bf16_path": float(diff8.mean()),
+        }
+        del ws_8, out_8
 
     if not args.no_probes:
         # what the device sustains: bf16 MFMA issue (two workgroups per CU, as the attention kernel

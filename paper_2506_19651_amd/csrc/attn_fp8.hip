@@ -217,8 +217,12 @@ __global__ __launch_bounds__(256) void quantise_kv_tiles_kernel(const uint16_t *
 }
 
 // ---------------------------------------------------------------- attend
+// Three wavefronts per SIMD (the second launch bound): it keeps the kernel within 168 registers, all of
+// them ordinary vector registers -- given more, the compiler parks the MFMA results in accumulation
+// registers and copies them back and forth around every softmax step (measured 24 % slower) -- and
+// lets the vector work of one wavefront run under the MFMAs of the others.
 template <int D>
-__global__ __launch_bounds__(256) void attn_fp8_kernel(Fp8Params p)
+__global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
 {
     constexpr int KT = kKeyTile, CPR = D / 16, TILEB = KT * D;
     constexpr int KQ = D / 64;            // score MFMAs (64 values of head_dim each) per 32-key chunk
