@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 MFMA_FP8_PEAK_TFLOPS = 5000.0   # ... dense fp8
 # HBM bytes per block-prefill launch from the FETCH_SIZE / WRITE_SIZE passes recorded in
 # profiles/attn_bf16_prefill_c3_counters.md (scaled by the same counters on a 1 GiB device copy)
-MEASURED_PREFILL_TRAFFIC_BYTES = {}
+MEASURED_PREFILL_TRAFFIC_BYTES = {("c3", "attn_bf16_stream_kernel<128>"): 1.280e9}
 HBM_PEAK_GBS = 8000.0
 
 
@@ -266,10 +266,25 @@ def main():
         dst = torch.empty(gib, dtype=torch.uint8, device=dev)
         ms_c = timed(lambda: P.pevlm_probe_copy(dst, src, gib, stream=stream), 5)
         mfma_rate = flops / (ms_m * 1e-3) / 1e12
+        # the kernels' own steady-state tile step in a bare loop (no per-item work, no masks): on the K
+        # tensor of the workload as data, with and without the softmax arithmetic
+        kv_probe = k[: 40 * 64].contiguous() if w.head_dim == 128 and w.n_kv_heads >= 1 else None
+        if kv_probe is not None and kv_probe.numel() * 2 >= 4 * 16384:
+            fl_t = P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream)
+            ms_t = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream), 5)
+            ms_t0 = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, False, stream=stream), 5)
+            tile_rate, tile_rate0 = fl_t / (ms_t * 1e-3) / 1e12, fl_t / (ms_t0 * 1e-3) / 1e12
         copy_rate = 2 * gib / (ms_c * 1e-3) / 1e9
         result["measured_peaks"] = {"mfma_bf16_tflops": round(mfma_rate, 1), "hbm_copy_gbs": round(copy_rate, 1),
                                     "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 workgroups/CU; 1 GiB device copy (read+write bytes)"}
         result["roofline"]["frac_of_measured_mfma_rate"] = round(result["roofline"]["achieved"] / mfma_rate, 4)
+        if kv_probe is not None:
+            result["measured_peaks"]["tile_loop_bf16_tflops"] = round(tile_rate, 1)
+            result["measured_peaks"]["tile_loop_bf16_tflops_without_softmax"] = round(tile_rate0, 1)
+            result["measured_peaks"]["tile_loop_how"] = ("the kernels' tile routines in a bare loop on workload data, 2 workgroups/CU: MFMAs, "
+                                                         "LDS fragment reads, global->LDS tile loads, barrier (+ weights arithmetic)")
+            # issued MFMA work of the real kernel (useful / unmasked share) against the bare loop
+            result["roofline"]["frac_of_tile_loop_rate"] = round(result["roofline"]["achieved"] / tile_rate, 4)
         result["rope_frac_of_measured_copy_rate"] = round(result["rope_gbs"] / copy_rate, 4)
         # question attention with K/V evicted: the 1 GiB copy (4x the 256 MB last-level cache) runs
         # right before each timed launch

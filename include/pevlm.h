@@ -341,10 +341,22 @@ pevlm_status pevlm_visible_pairs(const pevlm_layout *layout, int64_t *sink_pairs
  * operations of the launch.  scratch: DEVICE, >= 4 bytes, never written in practice.
  * pevlm_probe_copy: streaming copy of `bytes` (multiple of 16) from src to dst (DEVICE, 16-byte
  * aligned, not overlapping): bytes read + bytes written = 2*bytes.
- * Both enqueue one kernel on `stream` and return PEVLM_ERR_INVALID_ARG without launching on bad
+ * All probes enqueue one kernel on `stream` and return PEVLM_ERR_INVALID_ARG without launching on bad
  * arguments. */
 pevlm_status pevlm_probe_mfma_bf16(void *scratch, int32_t workgroups, int32_t iters, double *flop_count, void *stream);
 pevlm_status pevlm_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+/* pevlm_probe_tile_loop_bf16: the steady-state tile step of the bf16 block-prefill kernels and nothing
+ * else -- per step and wavefront 32 v_mfma_f32_32x32x16_bf16 (scores of a 32 x 64 x 128 tile and the
+ * values of the previous one), their LDS fragment reads, the asynchronous global->LDS loads of the next
+ * K and V tile, a workgroup barrier and, if with_softmax != 0, the vector arithmetic that turns the
+ * scores into bf16 weights -- run `iters` times by `workgroups` workgroups of 4 wavefronts (2 fit a
+ * compute unit).  No masks, no rescaling, no queries, no outputs: what this sustains is what the
+ * kernels' instruction mix allows on the device.  kv: DEVICE, 16-byte aligned, kv_bytes >= 64 KiB of
+ * finite bf16 data, read as 16 KiB tiles (first half as K tiles, second half as V tiles); scratch:
+ * DEVICE, >= 4 bytes, never written in practice; *flop_count (HOST, may be NULL) receives the
+ * floating-point operations of the MFMAs of the launch. */
+pevlm_status pevlm_probe_tile_loop_bf16(void *scratch, const void *kv, size_t kv_bytes, int32_t workgroups, int32_t iters,
+                                        int32_t with_softmax, double *flop_count, void *stream);
 
 #ifdef __cplusplus
 }

@@ -135,6 +135,8 @@ def load_library():
         lib.pevlm_rope_mrope.argtypes = [vp, vp, ctypes.c_int64, HP, ctypes.c_double, vp, ctypes.POINTER(ctypes.c_int32), vp]
         lib.pevlm_probe_mfma_bf16.restype = ctypes.c_int
         lib.pevlm_probe_mfma_bf16.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+        lib.pevlm_probe_tile_loop_bf16.restype = ctypes.c_int
+        lib.pevlm_probe_tile_loop_bf16.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
         lib.pevlm_probe_copy.restype = ctypes.c_int
         lib.pevlm_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.pevlm_visible_pairs.restype = ctypes.c_int
@@ -221,6 +223,14 @@ def pevlm_probe_mfma_bf16(scratch, workgroups: int, iters: int, stream=None) -> 
     """Enqueues the register-resident bf16 MFMA loop; returns the floating-point operations of the launch."""
     flops = ctypes.c_double(0.0)
     _check(load_library().pevlm_probe_mfma_bf16(_ptr(scratch), int(workgroups), int(iters), ctypes.byref(flops), _stream_ptr(stream)))
+    return float(flops.value)
+
+
+def pevlm_probe_tile_loop_bf16(scratch, kv, workgroups: int, iters: int, with_softmax: bool = True, stream=None) -> float:
+    """Enqueues the tile-loop probe on `kv` (a device tensor of finite bf16 data); returns the FLOPs of its MFMAs."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().pevlm_probe_tile_loop_bf16(_ptr(scratch), _ptr(kv), int(kv.numel() * kv.element_size()), int(workgroups),
+                                                     int(iters), int(bool(with_softmax)), ctypes.byref(flops), _stream_ptr(stream)))
     return float(flops.value)
 
 

@@ -1035,6 +1035,18 @@ pevlm_status pevlm_probe_mfma_bf16(void *scratch, int32_t workgroups, int32_t it
     return e == hipSuccess ? PEVLM_OK : hip_fail(e, "probe_mfma_kernel launch");
 }
 
+pevlm_status pevlm_probe_tile_loop_bf16(void *scratch, const void *kv, size_t kv_bytes, int32_t workgroups, int32_t iters,
+                                        int32_t with_softmax, double *flop_count, void *stream)
+{
+    const size_t tile = (size_t)kKeyTile * 128 * 2;
+    if (!scratch || !kv || !aligned16(kv) || kv_bytes < 4 * tile || kv_bytes / tile > 0x7fffffff || workgroups < 1 || iters < 1)
+        return fail(PEVLM_ERR_INVALID_ARG, "tile-loop probe needs scratch, a 16-byte aligned buffer of at least 4 tiles of 16 KiB, workgroups >= 1, iters >= 1");
+    if (flop_count) *flop_count = (double)workgroups * 4 * iters * 32 * 32768.0;
+    hipError_t e = launch_probe_tile_loop((float *)scratch, kv, (int32_t)(kv_bytes / tile), workgroups, iters, with_softmax != 0,
+                                          (hipStream_t)stream);
+    return e == hipSuccess ? PEVLM_OK : hip_fail(e, "tile-loop probe launch");
+}
+
 pevlm_status pevlm_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
     if (!dst || !src || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15) || bytes == 0 || (bytes & 15) || bytes > ((size_t)1 << 40))

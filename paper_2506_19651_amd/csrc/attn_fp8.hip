@@ -120,7 +120,21 @@ __global__ __launch_bounds__(256) void amax_kv_kernel(const uint16_t *k, const u
     const uint16_t *src = blockIdx.z ? v : k;
     const int32_t c = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
     float m = 0.f;
-    for (int64_t r = (int64_t)blockIdx.x * RPS + r0; r < T; r += (int64_t)gridDim.x * RPS) {
+    const int64_t step = (int64_t)gridDim.x * RPS;
+    int64_t r = (int64_t)blockIdx.x * RPS + r0;
+    for (; r + 3 * step < T; r += 4 * step) {  // four rows in flight per lane
+        uint4 raw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw[u] = *reinterpret_cast<const uint4 *>(src + ((r + u * step) * Hkv + g) * D + c * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float x[8];
+            bf16x8_to_f32(raw[u], x);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
+        }
+    }
+    for (; r < T; r += step) {
         const uint4 raw = *reinterpret_cast<const uint4 *>(src + (r * Hkv + g) * D + c * 8);
         float x[8];
         bf16x8_to_f32(raw, x);
@@ -129,7 +143,12 @@ __global__ __launch_bounds__(256) void amax_kv_kernel(const uint16_t *k, const u
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-    if ((threadIdx.x & 63) == 0) atomicMax(amax + blockIdx.z * Hkv + g, __float_as_uint(m));
+    // one atomic per workgroup: atomics on the same word are served one after the other
+    __shared__ float wave_max[4];
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        atomicMax(amax + blockIdx.z * Hkv + g, __float_as_uint(fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]))));
 }
 
 // Q: one scale per (token, head); D/16 consecutive lanes share a row of one head.

@@ -379,6 +379,8 @@ hipError_t launch_attn_bf16(const AttnParams &p, int32_t D, bool partial, hipStr
 hipError_t launch_merge(const MergeParams &p, hipStream_t stream);
 hipError_t launch_probe_mfma(float *sink, int32_t workgroups, int32_t iters, hipStream_t stream);
 hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t stream);
+hipError_t launch_probe_tile_loop(float *sink, const void *kv, int32_t n_tiles, int32_t workgroups, int32_t iters, bool weights,
+                                  hipStream_t stream);
 
 constexpr int32_t kTileRowsF32 = 16;   // query rows per work item of the fp32 kernels
 constexpr int32_t kTileRowsBf16 = 128; // query rows per work item of the bf16 MFMA kernels

@@ -1,7 +1,7 @@
 // Roofline probes: what this GPU sustains on the two resources the library's kernels are bound by.
 // They touch none of the method's arithmetic; the benchmark times them next to the real kernels so
 // that fractions can be quoted against the measured rates as well as the published peaks.
-#include "bf16_device.h"
+#include "attn_bf16_tile.h"
 
 namespace pevlm {
 
@@ -45,6 +45,105 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *__restrict__ dst
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         if (base + j * 256 < n16) dst[base + j * 256] = r[j];
+}
+
+// The steady-state tile step of the bf16 block-prefill kernels with everything per item taken away:
+// the same tile routines (scores of a tile with the next K tile requested piecewise, then the value
+// MFMAs of the previous tile interleaved with the weights of this one and the V loads), 4 wavefronts
+// per workgroup, 2 workgroups per compute unit, tiles of 64 keys x 128 fetched from `kv` round robin
+// (a few tiles: they stay in L2), no masks, no rescaling, no queries or outputs.  What it sustains is
+// the rate the kernels' instruction mix allows on this device; WEIGHTS = false leaves the softmax
+// arithmetic out (MFMAs, LDS fragment reads and tile loads only).
+template <bool WEIGHTS>
+__global__ __launch_bounds__(256, 2) void probe_tile_loop_kernel(float *sink, const uint8_t *kv, int32_t n_tiles, int32_t iters)
+{
+    constexpr int D = 128;
+    using C = TileCfg<D>;
+    constexpr int TILEB = C::TILEB, ROWB = C::ROWB, CH = C::CH, NLD = C::NLD;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[4 * TILEB];
+    const int32_t tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int32_t l32 = lane & 31, g32 = lane >> 5;
+    LaneOff L;
+    L.g32 = g32;
+    L.k_row_off = l32 * ROWB;
+    L.k_swz = l32 & (CH - 1);
+    L.v_row_off = (g32 * 4 + ((lane & 15) >> 2)) * ROWB + (lane & 1) * 8;
+    L.v_ch_lo = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+    L.v_swz = (lane >> 2) & C::VSW;
+    const uint32_t lds_addr = (uint32_t)(size_t)LDS_PTR(void, lds);
+    TileLoads<NLD> ldk, ldv;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int32_t row = (j * 4 + wave) * C::RPI + lane / CH, cpos = lane % CH;
+        ldk.off[j] = (uint32_t)(row * ROWB + ((cpos ^ (row & (CH - 1))) << 4));
+        ldv.off[j] = (uint32_t)(row * ROWB + ((cpos ^ ((row & C::VSW) << 2)) << 4));
+    }
+    // queries: the first rows of the buffer (any finite data will do)
+    bf16x8 qf[C::KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < C::KSTEPS; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8 *>(kv + (size_t)((blockIdx.x * 4 + wave) % 2) * TILEB + l32 * ROWB + (kk * 2 + g32) * 16);
+    f32x16 o[C::DBLK], s[2];
+    u32x4 pf_prev[4], pf_new[4];
+#pragma unroll
+    for (int b = 0; b < C::DBLK; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pf_prev[j][e] = 0x3c003c00u, pf_new[j][e] = 0x3c003c00u;
+    float l_run = 0.f;
+    const float c_log2 = 0.0883883f * 1.4426950408889634f, m_ref = 4.f;
+    const int32_t half = n_tiles / 2;  // K tiles in the first half of the buffer, V tiles in the second
+    // tile 0 of both tensors, then the loop: K(t+1) during the scores of tile t, V(t+1) during its weights
+    {
+        const uint8_t *kb = uniform_ptr(kv), *vb = uniform_ptr(kv + (size_t)half * TILEB);
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            load_lds_16_base(kb, ldk.off[j], lds_addr + (j * 4 + wave) * 1024);
+            load_lds_16_base(vb, ldv.off[j], lds_addr + 2 * TILEB + (j * 4 + wave) * 1024);
+        }
+    }
+    for (int32_t t = 0; t < iters; ++t) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const int32_t nt = (t + 1 + blockIdx.x) % half;
+        ldk.base = uniform_ptr(kv + (size_t)nt * TILEB);
+        ldv.base = uniform_ptr(kv + (size_t)(half + nt) * TILEB);
+        ldk.lds = lds_addr + ((t + 1) & 1) * TILEB + wave * 1024;
+        ldv.lds = lds_addr + (2 + ((t + 1) & 1)) * TILEB + wave * 1024;
+        qk_tile<D, true>(lds + (t & 1) * TILEB, L, qf, s, ldk);
+        float psum = 0.f;
+        if (WEIGHTS) {
+            pv_prev_weights_cur<D>(lds + (2 + (t & 1)) * TILEB, L, pf_prev, o, s, c_log2, m_ref, psum, pf_new, ldv);
+        } else {
+            // value MFMAs and V loads only; the scores stay live through one cheap use
+            pv_tile<D>(lds + (2 + (t & 1)) * TILEB, L, pf_prev, o);
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) load_lds_16_base(ldv.base, ldv.off[j], ldv.lds + j * 4096);
+            psum = s[0][0] + s[1][15];
+        }
+        l_run += psum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pf_prev[j] = pf_new[j];
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    float r = l_run;
+#pragma unroll
+    for (int b = 0; b < C::DBLK; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r += o[b][i];
+    if (r == -12345.678f) sink[0] = r;  // practically never true; keeps the results alive
+}
+
+hipError_t launch_probe_tile_loop(float *sink, const void *kv, int32_t n_tiles, int32_t workgroups, int32_t iters, bool weights,
+                                  hipStream_t stream)
+{
+    if (weights) hipLaunchKernelGGL((probe_tile_loop_kernel<true>), dim3(workgroups), dim3(256), 0, stream, sink, (const uint8_t *)kv, n_tiles, iters);
+    else hipLaunchKernelGGL((probe_tile_loop_kernel<false>), dim3(workgroups), dim3(256), 0, stream, sink, (const uint8_t *)kv, n_tiles, iters);
+    return hipGetLastError();
 }
 
 hipError_t launch_probe_mfma(float *sink, int32_t workgroups, int32_t iters, hipStream_t stream)

@@ -362,6 +362,19 @@ def test_roofline_probes_run_and_copy_is_exact():
         P.pevlm_probe_copy(dst, src, 24)
     with pytest.raises(P.PevlmError):
         P.pevlm_probe_mfma_bf16(scratch, 0, 10)
+    # the tile-loop probe: reads only inside the buffer it is given (guard bands around it stay intact and
+    # the buffer itself is never written), reports its operation count, rejects a buffer below four tiles
+    tiles = 5
+    buf = torch.full((4096 + tiles * 16384 + 4096,), 0x3C, dtype=torch.uint8, device=DEV)
+    kv = buf[4096: 4096 + tiles * 16384].view(torch.bfloat16)
+    before = buf.clone()
+    for soft in (True, False):
+        flops = P.pevlm_probe_tile_loop_bf16(scratch, kv, 16, 7, soft)
+        torch.cuda.synchronize()
+        assert flops == 16 * 4 * 7 * 32 * 32768
+    assert torch.equal(buf, before) and float(scratch.abs().sum()) == 0.0
+    with pytest.raises(P.PevlmError):
+        P.pevlm_probe_tile_loop_bf16(scratch, kv[: 3 * 8192], 16, 7, True)
 
 
 # ------------------------------------------------------------------------------------ multimodal RoPE
