@@ -94,6 +94,44 @@ def main():
         if ev:
             ev[3].record(stream)
 
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts))
+
+    peaks = None
+    if not args.no_probes:
+        # What the device sustains, measured BEFORE the steps: bf16 MFMA issue (two workgroups per CU, as
+        # the attention kernel runs), a 1 GiB streaming copy (also the known-size kernel that scales the
+        # FETCH_SIZE / WRITE_SIZE counters of a profiler pass over this same command) and the kernels' own
+        # tile step in a bare loop (no per-item work, no masks; the K tensor of the workload as data), with
+        # and without the softmax arithmetic.  Running them first also means that the warm-up steps start
+        # on a device that has been under load for ~0.1 s: after an idle stretch the first ~35 launches of
+        # any kernel run 5-30 % slow while the clocks settle, which 5 warm-up steps alone do not cover.
+        scratch = torch.zeros(64, dtype=torch.float32, device=dev)
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        flops = P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream)
+        ms_m = timed(lambda: P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream), 5)
+        gib = 1 << 30
+        src = torch.empty(gib, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty(gib, dtype=torch.uint8, device=dev)
+        ms_c = timed(lambda: P.pevlm_probe_copy(dst, src, gib, stream=stream), 5)
+        peaks = {"mfma_bf16_tflops": flops / (ms_m * 1e-3) / 1e12, "hbm_copy_gbs": 2 * gib / (ms_c * 1e-3) / 1e9}
+        kv_probe = k[: 40 * 64].contiguous() if w.head_dim == 128 else None
+        if kv_probe is not None and kv_probe.numel() * 2 >= 4 * 16384:
+            fl_t = P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream)
+            ms_t = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream), 5)
+            ms_t0 = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, False, stream=stream), 5)
+            peaks["tile_loop"] = (fl_t / (ms_t * 1e-3) / 1e12, fl_t / (ms_t0 * 1e-3) / 1e12)
+
     # first pass: kept for the accuracy figures reported next to the timing (every later pass
     # computes the same output from the same once-rotated q, k)
     step()
@@ -241,49 +279,17 @@ def main():
         del ws_8, out_8
 
     if not args.no_probes:
-        # what the device sustains: bf16 MFMA issue (two workgroups per CU, as the attention kernel
-        # runs) and a 1 GiB streaming copy; the copy is also the known-size kernel that scales the
-        # FETCH_SIZE / WRITE_SIZE counters of a profiler pass over this same command
-        def timed(fn, reps):
-            fn()
-            torch.cuda.synchronize()
-            ts = []
-            for _ in range(reps):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                fn()
-                b.record(stream)
-                torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b))
-            return float(np.median(ts))
-
-        scratch = torch.zeros(64, dtype=torch.float32, device=dev)
-        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
-        flops = P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream)
-        ms_m = timed(lambda: P.pevlm_probe_mfma_bf16(scratch, 2 * n_cu, 8000, stream=stream), 5)
-        gib = 1 << 30
-        src = torch.empty(gib, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty(gib, dtype=torch.uint8, device=dev)
-        ms_c = timed(lambda: P.pevlm_probe_copy(dst, src, gib, stream=stream), 5)
-        mfma_rate = flops / (ms_m * 1e-3) / 1e12
-        # the kernels' own steady-state tile step in a bare loop (no per-item work, no masks): on the K
-        # tensor of the workload as data, with and without the softmax arithmetic
-        kv_probe = k[: 40 * 64].contiguous() if w.head_dim == 128 and w.n_kv_heads >= 1 else None
-        if kv_probe is not None and kv_probe.numel() * 2 >= 4 * 16384:
-            fl_t = P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream)
-            ms_t = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, True, stream=stream), 5)
-            ms_t0 = timed(lambda: P.pevlm_probe_tile_loop_bf16(scratch, kv_probe, 2 * n_cu, 2000, False, stream=stream), 5)
-            tile_rate, tile_rate0 = fl_t / (ms_t * 1e-3) / 1e12, fl_t / (ms_t0 * 1e-3) / 1e12
-        copy_rate = 2 * gib / (ms_c * 1e-3) / 1e9
+        mfma_rate, copy_rate = peaks["mfma_bf16_tflops"], peaks["hbm_copy_gbs"]
         result["measured_peaks"] = {"mfma_bf16_tflops": round(mfma_rate, 1), "hbm_copy_gbs": round(copy_rate, 1),
                                     "how": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 workgroups/CU; 1 GiB device copy (read+write bytes)"}
         result["roofline"]["frac_of_measured_mfma_rate"] = round(result["roofline"]["achieved"] / mfma_rate, 4)
-        if kv_probe is not None:
+        if "tile_loop" in peaks:
+            tile_rate, tile_rate0 = peaks["tile_loop"]
             result["measured_peaks"]["tile_loop_bf16_tflops"] = round(tile_rate, 1)
             result["measured_peaks"]["tile_loop_bf16_tflops_without_softmax"] = round(tile_rate0, 1)
             result["measured_peaks"]["tile_loop_how"] = ("the kernels' tile routines in a bare loop on workload data, 2 workgroups/CU: MFMAs, "
                                                          "LDS fragment reads, global->LDS tile loads, barrier (+ weights arithmetic)")
-            # issued MFMA work of the real kernel (useful / unmasked share) against the bare loop
+            # the real kernel's useful rate against the bare loop
             result["roofline"]["frac_of_tile_loop_rate"] = round(result["roofline"]["achieved"] / tile_rate, 4)
         result["rope_frac_of_measured_copy_rate"] = round(result["rope_gbs"] / copy_rate, 4)
         # question attention with K/V evicted: the 1 GiB copy (4x the 256 MB last-level cache) runs
