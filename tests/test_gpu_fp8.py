@@ -185,6 +185,32 @@ def test_fp8_attention_against_oracle_over_the_quantised_tensors(oracle, name, H
     assert st["mean_abs"] <= 2e-2
 
 
+def test_fp8_with_a_head_map_and_a_caller_scale(oracle):
+    """Query heads mapped to KV heads out of order (unequal use would be legal too) and a softmax factor
+    other than 1/sqrt(d): both reach the fp8 kernel through the per-lane exponent constant and the head tables."""
+    seqs = [(100, 160, 500, 7), (30, 64, 200, 0)]
+    kv_map = [1, 0, 0, 1, 1, 0, 1, 0]
+    w = W.Workload("fp8_map", 34, "bf16", 8, 2, 128, 1.0e6, seqs, 0.5)
+    data = W.generate(w)
+    lay, heads = layout_heads(w, kv_map, 0.2)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    P.pevlm_rope_seq(q, k, lay, heads, w.rope_base)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((w.total_tokens, 8), float("nan"), device=DEV)
+    P.pevlm_block_prefill_attn_fp8(q, k, v, out, lay, heads, lse=lse)
+    torch.cuda.synchronize()
+    rows = prefill_rows(w)
+    qd, kd, vd = F8.dequantised_qkv(bf16_bits_to_f64(host_bits(q)), bf16_bits_to_f64(host_bits(k)), bf16_bits_to_f64(host_bits(v)))
+    olay = oracle_layout(oracle, w)
+    want, want_lse = oracle.attn(qd[rows], kd, vd, olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=0.2)
+    mean_abs_v, _ = oracle.attn(qd[rows], kd, np.abs(vd), olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=0.2)
+    ridx = torch.from_numpy(rows).to(DEV)
+    check_fp8(to_host_f32(out[ridx]), to_host_f32(lse[ridx]), want, want_lse, mean_abs_v, float(np.abs(vd).max()),
+              max(S + B for (S, B, C, Q) in seqs), "head map, scale 0.2")
+    plain, _ = oracle.attn(qd[rows], kd, vd, olay, rows=rows)  # default map and scale: must differ
+    assert np.max(np.abs(plain - want)) > 0.05
+
+
 def test_fp8_c3_full_size_sampled_rows(oracle):
     """The configuration bench.py times: sampled rows (region edges, tile edges, random) against the oracle."""
     w = W.CONFIGS["c3"]
@@ -203,6 +229,37 @@ def test_fp8_c3_full_size_sampled_rows(oracle):
     check_fp8(to_host_f32(out[ridx]), to_host_f32(lse[ridx]), want, want_lse, mean_abs_v, vmax, S + B, "c3")
     data_rows = torch.arange(0, S + C, device=DEV)
     assert torch.isfinite(out[data_rows].float()).all()
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_fp8_writes_nothing_outside_out_lse_and_its_workspace(D):
+    """out, lse and the workspace (sized exactly as the size query says) sit between guard bands; the
+    inputs are not modified."""
+    def guarded(nbytes, guard=4096):
+        pad = (-nbytes) % 256
+        buf = torch.full((guard + nbytes + pad + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+        return buf, buf[guard:guard + nbytes]
+
+    seqs = [(130, 200, 777, 129), (0, 64, 320, 5), (17, 1000, 250, 0), (5, 3, 0, 200)]
+    w = W.Workload(f"fp8g_{D}", 33, "bf16", 8, 2, D, 1.0e6, seqs, 0.5)
+    data = W.generate(w)
+    lay, heads = layout_heads(w)
+    q, k, v = to_device(data["q"]), to_device(data["k"]), to_device(data["v"])
+    keep = [t.clone() for t in (q, k, v)]
+    sizes = dict(out=q.numel() * 2, lse=w.total_tokens * w.n_q_heads * 4, ws=P.pevlm_block_prefill_fp8_workspace_bytes(lay, heads))
+    bufs = {name: guarded(n) for name, n in sizes.items()}
+    out = bufs["out"][1].view(torch.bfloat16).view(q.shape)
+    lse = bufs["lse"][1].view(torch.float32).view(w.total_tokens, w.n_q_heads)
+    for _ in range(2):
+        P.pevlm_block_prefill_attn_fp8(q, k, v, out, lay, heads, lse=lse, workspace=bufs["ws"][1])
+    torch.cuda.synchronize()
+    for name, n in sizes.items():
+        buf = bufs[name][0]
+        assert bool((buf[:4096] == 0xA5).all()) and bool((buf[4096 + n + (-n) % 256:] == 0xA5).all()), f"guard band of {name} overwritten"
+    for a, b in zip(keep, (q, k, v)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    rows = torch.from_numpy(prefill_rows(w)).to(DEV)
+    assert torch.isfinite(out[rows].float()).all() and torch.isfinite(lse[rows]).all()
 
 
 def test_fp8_rejects_what_it_does_not_cover():

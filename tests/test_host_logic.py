@@ -372,3 +372,29 @@ def test_time_model_tracks_measured_runs_and_sink_block_choice():
         assert t[(1, 2)] < t[(1, 16)] and t[(1, 2)] < t[(16, 2)] and t[(4, 4)] < t[(8, 8)]
     finally:
         P.pevlm_set_prefill_kernel(prev)
+
+
+def test_fp8_plan_offsets_and_counts():
+    """Host side of the fp8 variant: the plan's counts equal the host enumerations, its parts are
+    256-byte aligned, in order, large enough and do not overlap; unsupported dtypes are refused."""
+    for (Hq, Hkv, D, seqs) in [(4, 2, 128, [(130, 200, 777, 9), (0, 64, 320, 5), (17, 100, 250, 0)]),
+                               (6, 3, 64, [(70, 33, 150, 4), (5, 64, 64, 0)]), (28, 4, 128, [(256, 1024, 65536, 128)])]:
+        lay = P.Layout.from_seqs(seqs)
+        heads = P.Heads(Hq, Hkv, D, "bf16")
+        plan = P.pevlm_block_prefill_fp8_plan(lay, heads)
+        T = sum(s + c + q for (s, b, c, q) in seqs)
+        assert plan.n_items == len(P.pevlm_prefill_worklist_host(lay, 128))
+        assert plan.n_key_tiles == len(P.pevlm_prefill_worklist_host(lay, 64))
+        parts = [("items", plan.n_items * 32), ("key_tiles", plan.n_key_tiles * 32), ("kv_amax", 2 * Hkv * 4),
+                 ("q_scales", T * Hq * 4), ("q_codes", T * Hq * D), ("k_tiles", plan.n_key_tiles * Hkv * 64 * D),
+                 ("v_tiles", plan.n_key_tiles * Hkv * 64 * D)]
+        end = 0
+        for name, size in parts:
+            off = getattr(plan, name)
+            assert off % 256 == 0 and off >= end, name
+            end = off + size
+        assert end <= plan.total - 256 and plan.total == P.pevlm_block_prefill_fp8_workspace_bytes(lay, heads)
+    with pytest.raises(P.PevlmError):
+        P.pevlm_block_prefill_fp8_plan(P.Layout.from_seqs([(8, 8, 16, 0)]), P.Heads(2, 1, 64, "f32"))
+    assert P.pevlm_block_prefill_fp8_workspace_bytes(P.Layout.from_seqs([(8, 8, 16, 0)]), P.Heads(2, 1, 64, "f32")) == 0
+
