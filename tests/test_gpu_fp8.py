@@ -211,6 +211,35 @@ def test_fp8_with_a_head_map_and_a_caller_scale(oracle):
     assert np.max(np.abs(plain - want)) > 0.05
 
 
+def test_fp8_batch_larger_than_one_sequence_table(oracle):
+    """130 packed sequences (the sequence table travels to the kernels in pieces of 48): the key-tile
+    numbering and the work list run on across the pieces; sequences without sink, without context,
+    blocks shorter than a tile."""
+    rng = np.random.default_rng(5)
+    seqs = []
+    for _ in range(130):
+        S, B = int(rng.integers(0, 40)), int(rng.integers(1, 50))
+        C = int(rng.integers(0, 120)) if rng.random() < 0.8 else 0
+        Q = int(rng.integers(0, 20))
+        seqs.append((S, B, C, Q if S + C + Q else 1))
+    w = W.Workload("fp8_many", 35, "bf16", 4, 2, 64, 1.0e4, seqs, 0.5)
+    data = W.generate(w)
+    lay, heads, q, k, v = rotated_inputs(w, data)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((w.total_tokens, 4), float("nan"), device=DEV)
+    ws = P.pevlm_block_prefill_attn_fp8(q, k, v, out, lay, heads, lse=lse)
+    torch.cuda.synchronize()
+    rows = prefill_rows(w)
+    want, want_lse, mean_abs_v, vmax = fp8_reference(oracle, w, host_bits(q), host_bits(k), host_bits(v), rows)
+    ridx = torch.from_numpy(rows).to(DEV)
+    check_fp8(to_host_f32(out[ridx]), to_host_f32(lse[ridx]), want, want_lse, mean_abs_v, vmax, max(S + B for (S, B, C, Q) in seqs), "130 sequences")
+    plan = P.pevlm_block_prefill_fp8_plan(lay, heads)
+    tiles = P.pevlm_prefill_worklist_host(lay, 64)
+    dev_tiles = ws.cpu().numpy()[plan.key_tiles: plan.key_tiles + len(tiles) * 32].view(np.int32).reshape(len(tiles), 8)
+    assert len(tiles) == plan.n_key_tiles > 130
+    assert np.array_equal(dev_tiles[:, :2], np.array([[t.q_start, t.q_rows] for t in tiles], np.int32))
+
+
 def test_fp8_c3_full_size_sampled_rows(oracle):
     """The configuration bench.py times: sampled rows (region edges, tile edges, random) against the oracle."""
     w = W.CONFIGS["c3"]
