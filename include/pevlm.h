@@ -278,11 +278,13 @@ int64_t pevlm_prefill_stream_items_host(const pevlm_layout *layout, const pevlm_
  * A tensor is stored as codes times a power-of-two scale 2^e, e the smallest integer with
  * amax * 2^-e <= 448 (amax: the largest magnitude the scale covers; e = 0 if that is 0; e within
  * [-100, 100]); codes are rounded to nearest, ties to even.  Q has one scale per (token, query
- * head), K and V one per KV head over all tokens of the call.  Inputs must be finite.
+ * head), K and V one per KV head over all tokens of the call.  What is quantised of Q is q * f with
+ * f = softmax factor * log2(e) (both float32, one float32 rounding per product): the scores of the
+ * quantised operands are then base-2 exponents.  Inputs must be finite.
  *
  * Workspace (DEVICE, 256-byte aligned, pevlm_block_prefill_fp8_workspace_bytes; byte offsets of its
  * parts from pevlm_block_prefill_fp8_plan):
- *   q_codes   [T][Hq][D] codes;  q_scales [T][Hq] fp32 scales (2^e)
+ *   q_codes   [T][Hq][D] codes of q * f;  q_scales [T][Hq] fp32 scales (2^e)
  *   kv_amax   [2][Hkv] fp32: largest magnitude of K, then of V, per KV head
  *   key_tiles n_key_tiles pevlm_work_item: (q_start, q_rows) = the token rows of key tile i; the
  *             tiles are the 64-row tiles of pevlm_prefill_worklist_host(layout, 64, ...)

@@ -12,7 +12,10 @@ its block-prefill step (Sec. "Formulations", Eq. 3-4) and is defined here, in pl
     depend on the precision the scaling is carried out in;
   * codes are rounded to nearest, ties to the even mantissa, magnitudes above 448 saturate;
   * Q has one scale per (token, query head), K and V one scale per KV head over all tokens;
-  * the attention itself is Eq. 3-4 evaluated exactly (fp64) on the de-quantised tensors.
+  * what is quantised of Q is q * f, f = softmax factor * log2(e) as a float32 number and the product
+    rounded once to float32 (the scores of the quantised operands are then base-2 exponents);
+  * the attention itself is Eq. 3-4 evaluated exactly (fp64) on the de-quantised tensors (Q divided
+    by f again).
 
 Nothing here is shared with the HIP path.
 """
@@ -85,18 +88,26 @@ def dequantise(codes: np.ndarray, e: np.ndarray) -> np.ndarray:
     return np.ldexp(decode(codes), e)
 
 
-def quantise_qkv(q: np.ndarray, k: np.ndarray, v: np.ndarray):
-    """q [T, Hq, D], k and v [T, Hkv, D] -> dict of codes and scale exponents as the fp8 variant
-    stores them: Q per (token, head), K and V per head."""
+def q_factor(softmax_scale: float, head_dim: int) -> np.float32:
+    """f = softmax factor * log2(e) in float32 (softmax_scale <= 0: the default 1/sqrt(head_dim))."""
+    scale = np.float32(softmax_scale) if softmax_scale > 0 else np.float32(1.0 / np.sqrt(np.float64(head_dim)))
+    return np.float32(scale * np.float32(1.4426950408889634))
+
+
+def quantise_qkv(q: np.ndarray, k: np.ndarray, v: np.ndarray, factor: np.float32):
+    """q [T, Hq, D], k and v [T, Hkv, D] (values exactly representable in float32) -> dict of codes and
+    scale exponents as the fp8 variant stores them: Q * factor per (token, head), K and V per head."""
+    q = (np.asarray(q, np.float32) * np.float32(factor)).astype(np.float64)  # one float32 rounding per element
     qc, qe = quantise(q, axes=(2,))
     kc, ke = quantise(k, axes=(0, 2))
     vc, ve = quantise(v, axes=(0, 2))
     return dict(q_codes=qc, q_exp=qe[:, :, 0], k_codes=kc, k_exp=ke[0, :, 0], v_codes=vc, v_exp=ve[0, :, 0])
 
 
-def dequantised_qkv(q: np.ndarray, k: np.ndarray, v: np.ndarray):
-    """The tensors the fp8 variant attends over, as float64."""
-    z = quantise_qkv(q, k, v)
-    return (np.ldexp(decode(z["q_codes"]), z["q_exp"][:, :, None]),
+def dequantised_qkv(q: np.ndarray, k: np.ndarray, v: np.ndarray, factor: np.float32):
+    """The tensors the fp8 variant attends over, as float64 (Q with the factor taken out again, so that
+    the plain attention with the same softmax factor applies)."""
+    z = quantise_qkv(q, k, v, factor)
+    return (np.ldexp(decode(z["q_codes"]), z["q_exp"][:, :, None]) / np.float64(factor),
             np.ldexp(decode(z["k_codes"]), z["k_exp"][None, :, None]),
             np.ldexp(decode(z["v_codes"]), z["v_exp"][None, :, None]))

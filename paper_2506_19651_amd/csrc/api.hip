@@ -672,7 +672,8 @@ pevlm_status pevlm_block_prefill_attn_fp8(const void *q, const void *k, const vo
             }
             item_offset += tab.item_base[n];
         }
-        hipError_t e = launch_fp8_quantise(q, k, v, T, heads->n_q_heads, heads->n_kv_heads, heads->head_dim, key_tiles,
+        hipError_t e = launch_fp8_quantise(q, k, v, T, heads->n_q_heads, heads->n_kv_heads, heads->head_dim,
+                                           scale_of(heads) * 1.4426950408889634f, key_tiles,
                                            (int32_t)plan.n_key_tiles, (uint32_t *)(ws + plan.kv_amax), (float *)(ws + plan.q_scales),
                                            (uint8_t *)(ws + plan.q_codes), (uint8_t *)(ws + plan.k_tiles),
                                            (uint8_t *)(ws + plan.v_tiles), compute_units(), hs);

@@ -13,6 +13,11 @@
 //              a K tile and a V tile per step are copied into LDS (two stages each) by asynchronous
 //              global->LDS loads issued one tile ahead.
 //
+// Scores.  Q is quantised after multiplication by c = softmax factor * log2(e); the power-of-two scales of
+// the query row and of the K head enter the score MFMAs as their 8-bit block exponents, and the
+// accumulators start from 7 - m (m: the row's reference maximum): the MFMAs deliver the exponents of the
+// weights, and the vector ALU is left with exp2, the row sum, the row maximum and the conversion.
+//
 // Weights.  p = exp2(c s - m + 7) is rounded to E4M3; m is a reference maximum of the row that is
 // raised to the running maximum whenever that has outgrown it by more than one octave, so the
 // largest weight of a row lies in [2^7, 2^8] (E4M3 reaches 448) and weights down to 2^-16 of the
@@ -151,9 +156,11 @@ __global__ __launch_bounds__(256) void amax_kv_kernel(const uint16_t *k, const u
         atomicMax(amax + blockIdx.z * Hkv + g, __float_as_uint(fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]))));
 }
 
-// Q: one scale per (token, head); D/16 consecutive lanes share a row of one head.
+// Q: one scale per (token, head); D/16 consecutive lanes share a row of one head.  What is quantised is
+// q * factor (factor = softmax factor * log2(e), one fp32 multiplication per element), so that the score
+// MFMAs deliver base-2 exponents.
 template <int D>
-__global__ __launch_bounds__(256) void quantise_q_kernel(const uint16_t *q, int64_t n_rows_heads, uint8_t *codes, float *scales)
+__global__ __launch_bounds__(256) void quantise_q_kernel(const uint16_t *q, int64_t n_rows_heads, float factor, uint8_t *codes, float *scales)
 {
     constexpr int LPR = D / 16;  // lanes per row of one head
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -165,6 +172,8 @@ __global__ __launch_bounds__(256) void quantise_q_kernel(const uint16_t *q, int6
         const uint4 *src = reinterpret_cast<const uint4 *>(q + rh * D + c * 16);
         bf16x8_to_f32(src[0], x);
         bf16x8_to_f32(src[1], x + 8);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = __fmul_rn(x[i], factor);
     } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = 0.f;
@@ -296,9 +305,12 @@ __global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
             qf[kk] = i32x8{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
         }
     }
-    const float k_scale = pow2(scale_exponent(__uint_as_float(p.kv_amax[g])));
+    // The scales of K (per head) and of the query row (per lane: both halves of the wavefront hold the same
+    // rows) go into the score MFMAs as 8-bit exponents; the accumulators start from kWeightShift minus the
+    // row's reference maximum, so the MFMAs deliver the exponents of the weights directly.
+    const int32_t k_exp8 = 127 + scale_exponent(__uint_as_float(p.kv_amax[g]));
+    const int32_t q_exp8 = (__float_as_int(p.q_scales[(int64_t)my_row * Hq + head]) >> 23) & 0xff;
     const float v_scale = pow2(scale_exponent(__uint_as_float(p.kv_amax[Hkv + g])));
-    const float cq = p.scale * 1.4426950408889634f * p.q_scales[(int64_t)my_row * Hq + head] * k_scale;
 
     f32x16 o[DBLK], s[2];
 #pragma unroll
@@ -306,6 +318,10 @@ __global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
     float m_ref = -INFINITY, l_run = 0.f;
+    float shift = kWeightShift;  // kWeightShift - (reference maximum, 0 while the row has none)
+    f32x16 start;                // the same in all 16 accumulator registers of the lane
+#pragma unroll
+    for (int i = 0; i < 16; ++i) start[i] = shift;
 
     for (int32_t t = 0; t < n_tiles; ++t) {
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile t has landed
@@ -324,8 +340,7 @@ __global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
                 const i32x4v a = *reinterpret_cast<const i32x4v *>(tk + r * D + swizzled_chunk<CPR>(r, c0) * 16);
                 const i32x4v b = *reinterpret_cast<const i32x4v *>(tk + r * D + swizzled_chunk<CPR>(r, c0 + 1) * 16);
                 const i32x8 kf = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                s[kc] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[kk], kk == 0 ? zero : s[kc], 0, 0, 0, 0, 0, 0);
+                s[kc] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[kk], kk == 0 ? start : s[kc], 0, 0, 0, k_exp8, 0, q_exp8);
             }
         }
         int32_t k0, kend;
@@ -337,7 +352,7 @@ __global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
         }
         if ((k0 + KT > kend) || (causal && (k0 + KT - 1 > wr_lo))) mask_tile(s, k0, kend, causal, my_row, g32);
         // ---- reference maximum: raised to the running maximum once that is more than kWeightLag above it
-        const float mx = row_max(s) * cq;
+        const float mx = row_max(s) - shift;
         const bool raise = mx > m_ref + kWeightLag;
         if (__any(raise)) {
             const float m_new = raise ? mx : m_ref;
@@ -348,19 +363,28 @@ __global__ __launch_bounds__(256, 3) void attn_fp8_kernel(Fp8Params p)
             for (int b = 0; b < DBLK; ++b)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+            // the scores of this tile move to the new reference; later tiles start from it
+            const float new_shift = kWeightShift - ((m_ref == -INFINITY) ? 0.f : m_ref);
+            const float delta = new_shift - shift;
+            shift = new_shift;
+#pragma unroll
+            for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[kc][i] += delta;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) start[i] = shift;
         }
         // ---- weights: E4M3 codes in the order the value MFMA wants them (byte 16 kc + i of the lane)
-        const float shift = kWeightShift - ((m_ref == -INFINITY) ? 0.f : m_ref);
         float psum = 0.f;
         i32x8 pf;
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float w0 = __builtin_amdgcn_exp2f(fmaf(s[kc][4 * w], cq, shift));
-                const float w1 = __builtin_amdgcn_exp2f(fmaf(s[kc][4 * w + 1], cq, shift));
-                const float w2 = __builtin_amdgcn_exp2f(fmaf(s[kc][4 * w + 2], cq, shift));
-                const float w3 = __builtin_amdgcn_exp2f(fmaf(s[kc][4 * w + 3], cq, shift));
+                const float w0 = __builtin_amdgcn_exp2f(s[kc][4 * w]);
+                const float w1 = __builtin_amdgcn_exp2f(s[kc][4 * w + 1]);
+                const float w2 = __builtin_amdgcn_exp2f(s[kc][4 * w + 2]);
+                const float w3 = __builtin_amdgcn_exp2f(s[kc][4 * w + 3]);
                 psum += (w0 + w1) + (w2 + w3);
                 pf[kc * 4 + w] = pack2<true>(w2, w3, pack2<false>(w0, w1, 0));
             }
@@ -417,7 +441,7 @@ hipError_t launch_build_fp8_items(const SeqTable &tab, const Fp8TileBases &bases
 }
 
 hipError_t launch_fp8_quantise(const void *q, const void *k, const void *v, int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
-                               const pevlm_work_item *key_tiles, int32_t n_key_tiles, uint32_t *kv_amax, float *q_scales,
+                               float q_factor, const pevlm_work_item *key_tiles, int32_t n_key_tiles, uint32_t *kv_amax, float *q_scales,
                                uint8_t *q_codes, uint8_t *k_tiles, uint8_t *v_tiles, int32_t compute_units, hipStream_t stream)
 {
     hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(256), 0, stream, kv_amax, 2 * Hkv);
@@ -427,12 +451,12 @@ hipError_t launch_fp8_quantise(const void *q, const void *k, const void *v, int6
     const dim3 q_grid((uint32_t)((q_threads + 255) / 256));
     if (D == 128) {
         hipLaunchKernelGGL((amax_kv_kernel<128>), dim3(bx, Hkv, 2), dim3(256), 0, stream, (const uint16_t *)k, (const uint16_t *)v, T, Hkv, kv_amax);
-        hipLaunchKernelGGL((quantise_q_kernel<128>), q_grid, dim3(256), 0, stream, (const uint16_t *)q, T * Hq, q_codes, q_scales);
+        hipLaunchKernelGGL((quantise_q_kernel<128>), q_grid, dim3(256), 0, stream, (const uint16_t *)q, T * Hq, q_factor, q_codes, q_scales);
         hipLaunchKernelGGL((quantise_kv_tiles_kernel<128>), dim3(n_key_tiles, Hkv), dim3(256), 0, stream, (const uint16_t *)k,
                            (const uint16_t *)v, key_tiles, Hkv, kv_amax, k_tiles, v_tiles);
     } else {
         hipLaunchKernelGGL((amax_kv_kernel<64>), dim3(bx, Hkv, 2), dim3(256), 0, stream, (const uint16_t *)k, (const uint16_t *)v, T, Hkv, kv_amax);
-        hipLaunchKernelGGL((quantise_q_kernel<64>), q_grid, dim3(256), 0, stream, (const uint16_t *)q, T * Hq, q_codes, q_scales);
+        hipLaunchKernelGGL((quantise_q_kernel<64>), q_grid, dim3(256), 0, stream, (const uint16_t *)q, T * Hq, q_factor, q_codes, q_scales);
         hipLaunchKernelGGL((quantise_kv_tiles_kernel<64>), dim3(n_key_tiles, Hkv), dim3(256), 0, stream, (const uint16_t *)k,
                            (const uint16_t *)v, key_tiles, Hkv, kv_amax, k_tiles, v_tiles);
     }

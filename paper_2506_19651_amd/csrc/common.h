@@ -371,7 +371,7 @@ hipError_t launch_attn_bf16_stream(const StreamParams &p, int32_t D, int32_t com
 hipError_t launch_build_fp8_items(const SeqTable &tab, const Fp8TileBases &bases, Fp8Item *items, int32_t item_offset, hipStream_t stream);
 // bf16 Q, K, V -> E4M3 codes and scales (key_tiles: the prefill items of 64 rows, one per K/V tile)
 hipError_t launch_fp8_quantise(const void *q, const void *k, const void *v, int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
-                               const pevlm_work_item *key_tiles, int32_t n_key_tiles, uint32_t *kv_amax, float *q_scales,
+                               float q_factor, const pevlm_work_item *key_tiles, int32_t n_key_tiles, uint32_t *kv_amax, float *q_scales,
                                uint8_t *q_codes, uint8_t *k_tiles, uint8_t *v_tiles, int32_t compute_units, hipStream_t stream);
 hipError_t launch_attn_fp8(const Fp8Params &p, int32_t D, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams &p, int32_t D, bool partial, hipStream_t stream);

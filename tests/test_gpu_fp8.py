@@ -100,7 +100,7 @@ def test_fp8_codes_scales_and_tile_images_bit_for_bit(name, Hq, Hkv, D, seqs):
     plan = P.pevlm_block_prefill_fp8_plan(lay, heads)
     raw = ws.cpu().numpy()
     T = w.total_tokens
-    ref = F8.quantise_qkv(bf16_bits_to_f64(data["q"]), bf16_bits_to_f64(data["k"]), bf16_bits_to_f64(data["v"]))
+    ref = F8.quantise_qkv(bf16_bits_to_f64(data["q"]), bf16_bits_to_f64(data["k"]), bf16_bits_to_f64(data["v"]), F8.q_factor(0.0, D))
     q_codes = raw[plan.q_codes: plan.q_codes + T * Hq * D].reshape(T, Hq, D)
     q_scales = raw[plan.q_scales: plan.q_scales + T * Hq * 4].view(np.float32).reshape(T, Hq)
     assert np.array_equal(q_codes, ref["q_codes"])
@@ -134,7 +134,8 @@ ATTN_CASES = [
 
 def fp8_reference(oracle, w, q_bits, k_bits, v_bits, rows):
     """Exact attention over the de-quantised tensors, and the same attention applied to |v|."""
-    qd, kd, vd = F8.dequantised_qkv(bf16_bits_to_f64(q_bits), bf16_bits_to_f64(k_bits), bf16_bits_to_f64(v_bits))
+    qd, kd, vd = F8.dequantised_qkv(bf16_bits_to_f64(q_bits), bf16_bits_to_f64(k_bits), bf16_bits_to_f64(v_bits),
+                                    F8.q_factor(0.0, w.head_dim))
     olay = oracle_layout(oracle, w)
     want, want_lse = oracle.attn(qd[rows], kd, vd, olay, rows=rows)
     mean_abs_v, _ = oracle.attn(qd[rows], kd, np.abs(vd), olay, rows=rows)
@@ -200,10 +201,12 @@ def test_fp8_with_a_head_map_and_a_caller_scale(oracle):
     P.pevlm_block_prefill_attn_fp8(q, k, v, out, lay, heads, lse=lse)
     torch.cuda.synchronize()
     rows = prefill_rows(w)
-    qd, kd, vd = F8.dequantised_qkv(bf16_bits_to_f64(host_bits(q)), bf16_bits_to_f64(host_bits(k)), bf16_bits_to_f64(host_bits(v)))
+    qd, kd, vd = F8.dequantised_qkv(bf16_bits_to_f64(host_bits(q)), bf16_bits_to_f64(host_bits(k)), bf16_bits_to_f64(host_bits(v)),
+                                    F8.q_factor(0.2, 128))
     olay = oracle_layout(oracle, w)
-    want, want_lse = oracle.attn(qd[rows], kd, vd, olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=0.2)
-    mean_abs_v, _ = oracle.attn(qd[rows], kd, np.abs(vd), olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=0.2)
+    s32 = float(np.float32(0.2))
+    want, want_lse = oracle.attn(qd[rows], kd, vd, olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=s32)
+    mean_abs_v, _ = oracle.attn(qd[rows], kd, np.abs(vd), olay, rows=rows, kv_head_of_q=kv_map, softmax_scale=s32)
     ridx = torch.from_numpy(rows).to(DEV)
     check_fp8(to_host_f32(out[ridx]), to_host_f32(lse[ridx]), want, want_lse, mean_abs_v, float(np.abs(vd).max()),
               max(S + B for (S, B, C, Q) in seqs), "head map, scale 0.2")

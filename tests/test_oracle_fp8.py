@@ -84,7 +84,10 @@ def test_scale_granularity_and_error_bound():
     q = rng.standard_normal((T, Hq, D)) * 0.5
     k = rng.standard_normal((T, Hkv, D)) * 0.5
     v = rng.standard_normal((T, Hkv, D)) * 0.5
-    z = F8.quantise_qkv(q, k, v)
+    f = F8.q_factor(0.0, D)
+    assert f == np.float32(np.float32(1.0 / np.sqrt(64.0)) * np.float32(1.4426950408889634))
+    q = q.astype(np.float32).astype(np.float64)  # the reference takes float32-representable values
+    z = F8.quantise_qkv(q, k, v, f)
     assert z["q_exp"].shape == (T, Hq) and z["k_exp"].shape == (Hkv,) and z["v_exp"].shape == (Hkv,)
     # the largest element of every scaled slice lands in [224, 448]
     assert np.all(np.abs(F8.decode(z["q_codes"])).max(axis=2) >= 224)
@@ -92,20 +95,21 @@ def test_scale_granularity_and_error_bound():
     # one large value in K: its head changes scale for every token, the other head and Q do not
     k2 = k.copy()
     k2[5, 1, 3] = 1000.0
-    z2 = F8.quantise_qkv(q, k2, v)
+    z2 = F8.quantise_qkv(q, k2, v, f)
     assert z2["k_exp"][1] > z["k_exp"][1] and z2["k_exp"][0] == z["k_exp"][0]
     assert np.array_equal(z2["k_codes"][:, 0], z["k_codes"][:, 0]) and not np.array_equal(z2["k_codes"][:, 1], z["k_codes"][:, 1])
     assert np.array_equal(z2["q_codes"], z["q_codes"])
     # one large value in a Q row: only that (token, head) changes
     q2 = q.copy()
     q2[9, 2, 0] = 77.0
-    z3 = F8.quantise_qkv(q2, k, v)
+    z3 = F8.quantise_qkv(q2, k, v, f)
     same = np.ones((T, Hq), bool)
     same[9, 2] = False
     assert np.array_equal(z3["q_codes"][same], z["q_codes"][same]) and z3["q_exp"][9, 2] > z["q_exp"][9, 2]
     # normal-range elements keep a relative error of at most 2^-4 (half a unit of a 3-bit mantissa)
-    qd, kd, vd = F8.dequantised_qkv(q, k, v)
-    for x, xd, e in ((q, qd, z["q_exp"][:, :, None]), (k, kd, z["k_exp"][None, :, None]), (v, vd, z["v_exp"][None, :, None])):
+    qd, kd, vd = F8.dequantised_qkv(q, k, v, f)
+    qs = (q.astype(np.float32) * f).astype(np.float64)  # what is quantised of Q
+    for x, xd, e in ((qs, qd * np.float64(f), z["q_exp"][:, :, None]), (k, kd, z["k_exp"][None, :, None]), (v, vd, z["v_exp"][None, :, None])):
         normal = np.abs(x) >= np.ldexp(1.0, e - 6)
         assert np.all(np.abs(xd - x)[normal] <= 2.0 ** -4 * np.abs(x)[normal])
         assert np.all(np.abs(xd - x)[~normal] <= np.broadcast_to(np.ldexp(1.0, e - 10), x.shape)[~normal])
